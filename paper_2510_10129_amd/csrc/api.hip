@@ -1,0 +1,374 @@
+// C ABI of the library: argument checks, workspace, stream and kernel timing.
+// Every compute step runs in the HIP kernels of this directory.
+#include <math.h>
+#include <string.h>
+
+#include "cc_internal.h"
+
+namespace {
+
+thread_local std::string g_create_err;
+
+cc_status fail(cc_ctx* c, cc_status code, const std::string& msg) {
+    if (c) c->err = msg; else g_create_err = msg;
+    return code;
+}
+
+#define CC_HIP(c, call)                                                                       \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail((c), CC_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+cc_status check_model(const cc_model_desc& m, std::string* why) {
+    auto bad = [&](const char* s) { *why = s; return CC_ERR_SHAPE; };
+    if (m.d < 64 || m.d % 64) return bad("d must be a positive multiple of 64");
+    if (m.f < 64 || m.f % 64) return bad("f must be a positive multiple of 64");
+    if (m.d_h != 64 && m.d_h != 128) return bad("d_h must be 64 or 128");
+    if (m.H_q < 1 || m.H_kv < 1 || m.H_q % m.H_kv) return bad("H_kv must divide H_q");
+    if (m.H_q / m.H_kv > 32) return bad("H_q / H_kv must be <= 32");
+    if (!(m.rope_base > 1.0f)) return bad("rope_base must be > 1");
+    if (!(m.rms_eps >= 0.0f)) return bad("rms_eps must be >= 0");
+    if (m.N_cap < 1 || m.M_cap < 1 || m.T_cap < 1) return bad("capacities must be >= 1");
+    if (m.T_cap > 131072) return bad("T_cap must be <= 131072");
+    return CC_OK;
+}
+
+cc_status check_kv(cc_ctx* c, const cc_kv_layer* kv) {
+    if (!kv || !kv->K || !kv->V) return fail(c, CC_ERR_NULL, "kv, kv->K and kv->V must not be NULL");
+    if (kv->N < 1 || kv->N > c->m.N_cap)
+        return fail(c, CC_ERR_WORKSPACE, "kv->N must be in [1, N_cap]");
+    if (kv->stride_head < c->m.d_h || kv->stride_head % 8 ||
+        kv->stride_token < (int64_t)c->m.d_h * c->m.H_kv || kv->stride_token % 8)
+        return fail(c, CC_ERR_SHAPE, "kv strides must be multiples of 8 and cover [H_kv, d_h]");
+    if (!aligned16(kv->K) || !aligned16(kv->V))
+        return fail(c, CC_ERR_SHAPE, "kv->K and kv->V must be 16-byte aligned");
+    return CC_OK;
+}
+
+cc_status check_rows(cc_ctx* c, int32_t M) {
+    if (M < 0) return fail(c, CC_ERR_SHAPE, "M must be >= 0");
+    if (M > c->m.M_cap) return fail(c, CC_ERR_WORKSPACE, "M exceeds M_cap");
+    return CC_OK;
+}
+
+// Optional device-side check of idx / gather_idx; synchronises the stream.
+cc_status check_idx_sync(cc_ctx* c, const int32_t* idx, int M, int hi, int strict, const char* what) {
+    if (M <= 0 || !idx) return CC_OK;
+    CC_HIP(c, hipMemsetAsync(c->flag, 0, sizeof(int32_t), c->stream));
+    cc_launch_check_idx(idx, M, 0, hi, strict, c->flag, c->stream);
+    CC_HIP(c, hipMemcpyAsync(c->pinned, c->flag, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    CC_HIP(c, hipStreamSynchronize(c->stream));
+    if (c->pinned[0] != 0)
+        return fail(c, CC_ERR_IDX, std::string(what) + (strict ? " must be strictly ascending and in range"
+                                                                : " must be in range"));
+    return CC_OK;
+}
+
+}  // namespace
+
+cc_prof_scope::cc_prof_scope(cc_ctx* ctx, int kind) : c(ctx), on(ctx->prof) {
+    if (!on) return;
+    if (c->pool.empty()) {
+        cc_event_pair np;
+        if (hipEventCreate(&np.a) != hipSuccess || hipEventCreate(&np.b) != hipSuccess) {
+            on = false;
+            return;
+        }
+        p = np;
+    } else {
+        p = c->pool.back();
+        c->pool.pop_back();
+    }
+    p.kind = kind;
+    (void)hipEventRecord(p.a, c->stream);
+}
+
+cc_prof_scope::~cc_prof_scope() {
+    if (!on) return;
+    (void)hipEventRecord(p.b, c->stream);
+    c->used.push_back(p);
+}
+
+extern "C" {
+
+const char* cc_last_error(const cc_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream) {
+    if (!out || !desc) return fail(nullptr, CC_ERR_NULL, "out and desc must not be NULL");
+    *out = nullptr;
+    std::string why;
+    if (check_model(*desc, &why) != CC_OK) return fail(nullptr, CC_ERR_SHAPE, why);
+    cc_ctx* c = new cc_ctx();
+    c->m = *desc;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->prof = false;
+    memset(c->prof_ms, 0, sizeof(c->prof_ms));
+    memset(c->prof_n, 0, sizeof(c->prof_n));
+    c->rope = nullptr; c->xn = nullptr; c->q = nullptr; c->o = nullptr; c->y = nullptr;
+    c->mn = nullptr; c->act = nullptr; c->score = nullptr; c->n_sel = nullptr; c->flag = nullptr;
+    c->pinned = nullptr;
+    const cc_model_desc& m = c->m;
+    const size_t Mc = (size_t)m.M_cap, nq = (size_t)m.H_q * m.d_h;
+    hipError_t e = hipGetDevice(&c->device);
+    auto alloc = [&](void** p, size_t bytes) {
+        if (e == hipSuccess) e = hipMalloc(p, bytes);
+    };
+    alloc((void**)&c->rope, (size_t)m.N_cap * (m.d_h / 2) * sizeof(float2));
+    alloc((void**)&c->xn, Mc * m.d * 2);
+    alloc((void**)&c->q, Mc * nq * 2);
+    alloc((void**)&c->o, Mc * nq * 2);
+    alloc((void**)&c->y, Mc * m.d * 4);
+    alloc((void**)&c->mn, Mc * m.d * 2);
+    alloc((void**)&c->act, Mc * m.f * 2);
+    alloc((void**)&c->score, (size_t)m.T_cap * 4);
+    alloc((void**)&c->n_sel, 4);
+    alloc((void**)&c->flag, 4);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&c->pinned, 2 * sizeof(int32_t), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        std::string msg = std::string("workspace allocation: ") + hipGetErrorString(e);
+        cc_destroy(c);
+        return fail(nullptr, CC_ERR_HIP, msg);
+    }
+    cc_launch_rope_table(c->rope, m.N_cap, m.d_h, (double)m.rope_base, c->stream);
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        std::string msg = std::string("rope table launch: ") + hipGetErrorString(e);
+        cc_destroy(c);
+        return fail(nullptr, CC_ERR_HIP, msg);
+    }
+    *out = c;
+    return CC_OK;
+}
+
+cc_status cc_destroy(cc_ctx* c) {
+    if (!c) return CC_OK;
+    (void)hipStreamSynchronize(c->stream);
+    for (auto& p : c->used) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+    for (auto& p : c->pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+    (void)hipFree(c->rope); (void)hipFree(c->xn); (void)hipFree(c->q); (void)hipFree(c->o);
+    (void)hipFree(c->y); (void)hipFree(c->mn); (void)hipFree(c->act); (void)hipFree(c->score);
+    (void)hipFree(c->n_sel); (void)hipFree(c->flag);
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    delete c;
+    return CC_OK;
+}
+
+cc_status cc_set_stream(cc_ctx* c, void* hip_stream) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    return CC_OK;
+}
+
+cc_status cc_step_column_scores(cc_ctx* c, const float* attn, int32_t Q_a, int32_t T, int64_t ld,
+                                float* score) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!attn || !score) return fail(c, CC_ERR_NULL, "attn and score must not be NULL");
+    if (Q_a < 1 || T < 1 || ld < T) return fail(c, CC_ERR_SHAPE, "need Q_a >= 1, T >= 1, ld >= T");
+    {
+        cc_prof_scope ps(c, CC_K_COLSUM);
+        cc_launch_colsum(attn, Q_a, T, ld, score, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
+cc_status cc_select(cc_ctx* c, const float* attn, int32_t Q_a, int32_t T, int64_t ld,
+                    uint32_t recomp_bp, int32_t window, int32_t tau, int32_t flags,
+                    int32_t idx_offset, int32_t n_tail, int32_t* idx_out, int32_t* n_out,
+                    int32_t* n_out_host) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!attn || !idx_out || !n_out) return fail(c, CC_ERR_NULL, "attn, idx_out and n_out must not be NULL");
+    if (Q_a < 1 || T < 1 || ld < T) return fail(c, CC_ERR_SHAPE, "need Q_a >= 1, T >= 1, ld >= T");
+    if (T > c->m.T_cap) return fail(c, CC_ERR_WORKSPACE, "T exceeds T_cap");
+    if (recomp_bp > 10000u) return fail(c, CC_ERR_SHAPE, "recomp_bp must be <= 10000");
+    if (window < 1 || window > 1024) return fail(c, CC_ERR_SHAPE, "window must be in [1, 1024]");
+    if (tau < 0 || tau > window) return fail(c, CC_ERR_SHAPE, "tau must be in [0, window]");
+    if (n_tail < 0 || idx_offset < 0) return fail(c, CC_ERR_SHAPE, "idx_offset and n_tail must be >= 0");
+    const int k = (int)(((int64_t)T * (int64_t)recomp_bp) / 10000);
+    const int tau_eff = tau > 0 ? tau : (5 * window + 7) / 8;
+    {
+        cc_prof_scope ps(c, CC_K_COLSUM);
+        cc_launch_colsum(attn, Q_a, T, ld, c->score, c->stream);
+    }
+    {
+        cc_prof_scope ps(c, CC_K_SELECT);
+        cc_launch_select(c->score, T, k, window, tau_eff, (flags & CC_FLAG_NO_GROUPING) ? 0 : 1,
+                         idx_offset, n_tail, idx_out, n_out, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    if (n_out_host) {
+        CC_HIP(c, hipMemcpyAsync(c->pinned + 1, n_out, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        CC_HIP(c, hipStreamSynchronize(c->stream));
+        *n_out_host = c->pinned[1];
+    }
+    return CC_OK;
+}
+
+cc_status cc_step_gather_rmsnorm(cc_ctx* c, const void* hidden, int64_t rows,
+                                 const int32_t* gather_idx, int32_t M, const void* w_norm, void* xn) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!hidden || !w_norm || !xn) return fail(c, CC_ERR_NULL, "hidden, w_norm and xn must not be NULL");
+    if (M < 0 || rows < 1 || (!gather_idx && rows < M)) return fail(c, CC_ERR_SHAPE, "bad M / rows");
+    if (!aligned16(hidden) || !aligned16(w_norm) || !aligned16(xn))
+        return fail(c, CC_ERR_SHAPE, "buffers must be 16-byte aligned");
+    {
+        cc_prof_scope ps(c, CC_K_GATHER_NORM);
+        cc_launch_gather_rmsnorm((const bf16_t*)hidden, gather_idx, M, c->m.d, (const bf16_t*)w_norm,
+                                 c->m.rms_eps, (bf16_t*)xn, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
+cc_status cc_step_qkv_rope_scatter(cc_ctx* c, const void* xn, int32_t M, const int32_t* idx,
+                                   const void* w_qkv, const void* b_qkv, const cc_kv_layer* kv,
+                                   void* q_out, int32_t flags) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!xn || !idx || !w_qkv || !q_out) return fail(c, CC_ERR_NULL, "xn, idx, w_qkv and q_out must not be NULL");
+    cc_status st = check_kv(c, kv);
+    if (st != CC_OK) return st;
+    if (M < 0) return fail(c, CC_ERR_SHAPE, "M must be >= 0");
+    if (!aligned16(xn) || !aligned16(w_qkv) || !aligned16(q_out) || (b_qkv && !aligned16(b_qkv)))
+        return fail(c, CC_ERR_SHAPE, "buffers must be 16-byte aligned");
+    if (flags & CC_FLAG_CHECK_IDX) {
+        st = check_idx_sync(c, idx, M, kv->N, 1, "idx");
+        if (st != CC_OK) return st;
+    }
+    {
+        cc_prof_scope ps(c, CC_K_QKV);
+        cc_launch_qkv((const bf16_t*)xn, M, idx, (const bf16_t*)w_qkv, (const bf16_t*)b_qkv, c->m,
+                      c->rope, *kv, (bf16_t*)q_out, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
+cc_status cc_step_sparse_attention(cc_ctx* c, const void* q, int32_t M, const int32_t* idx,
+                                   const cc_kv_layer* kv, void* o, int32_t flags) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!q || !idx || !o) return fail(c, CC_ERR_NULL, "q, idx and o must not be NULL");
+    cc_status st = check_kv(c, kv);
+    if (st != CC_OK) return st;
+    if (M < 0) return fail(c, CC_ERR_SHAPE, "M must be >= 0");
+    if (!aligned16(q) || !aligned16(o)) return fail(c, CC_ERR_SHAPE, "buffers must be 16-byte aligned");
+    if (flags & CC_FLAG_CHECK_IDX) {
+        st = check_idx_sync(c, idx, M, kv->N, 1, "idx");
+        if (st != CC_OK) return st;
+    }
+    {
+        cc_prof_scope ps(c, CC_K_ATTN);
+        cc_launch_attention((const bf16_t*)q, M, idx, c->m, *kv, (bf16_t*)o, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
+cc_status cc_step_oproj_residual(cc_ctx* c, const void* o, int32_t M, const void* w_o,
+                                 const void* hidden, int64_t rows, const int32_t* gather_idx, float* y) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!o || !w_o || !hidden || !y) return fail(c, CC_ERR_NULL, "o, w_o, hidden and y must not be NULL");
+    if (M < 0 || rows < 1 || (!gather_idx && rows < M)) return fail(c, CC_ERR_SHAPE, "bad M / rows");
+    if (!aligned16(o) || !aligned16(w_o) || !aligned16(hidden) || !aligned16(y))
+        return fail(c, CC_ERR_SHAPE, "buffers must be 16-byte aligned");
+    {
+        cc_prof_scope ps(c, CC_K_OPROJ);
+        cc_launch_oproj((const bf16_t*)o, M, (const bf16_t*)w_o, (const bf16_t*)hidden, gather_idx,
+                        c->m, y, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
+cc_status cc_step_mlp(cc_ctx* c, const float* y, int32_t M, const void* w_post_norm,
+                      const void* w_gate, const void* w_up, const void* w_down, void* out) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!y || !w_post_norm || !w_gate || !w_up || !w_down || !out)
+        return fail(c, CC_ERR_NULL, "y, weights and out must not be NULL");
+    cc_status st = check_rows(c, M);
+    if (st != CC_OK) return st;
+    if (!aligned16(y) || !aligned16(w_post_norm) || !aligned16(w_gate) || !aligned16(w_up) ||
+        !aligned16(w_down) || !aligned16(out))
+        return fail(c, CC_ERR_SHAPE, "buffers must be 16-byte aligned");
+    {
+        cc_prof_scope ps(c, CC_K_POST_NORM);
+        cc_launch_rmsnorm_f32(y, M, c->m.d, (const bf16_t*)w_post_norm, c->m.rms_eps, c->mn, c->stream);
+    }
+    {
+        cc_prof_scope ps(c, CC_K_GATE_UP);
+        cc_launch_gate_up(c->mn, M, (const bf16_t*)w_gate, (const bf16_t*)w_up, c->m, c->act, c->stream);
+    }
+    {
+        cc_prof_scope ps(c, CC_K_DOWN);
+        cc_launch_down(c->act, M, (const bf16_t*)w_down, y, c->m, (bf16_t*)out, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
+cc_status cc_recompute_layer(cc_ctx* c, const void* hidden, int64_t rows, const int32_t* gather_idx,
+                             const cc_kv_layer* kv, const int32_t* idx, int32_t M,
+                             const cc_layer_weights* w, void* out, int32_t flags) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!hidden || !idx || !w || !out) return fail(c, CC_ERR_NULL, "hidden, idx, w and out must not be NULL");
+    if (!w->w_in_norm || !w->w_qkv || !w->w_o || !w->w_post_norm || !w->w_gate || !w->w_up || !w->w_down)
+        return fail(c, CC_ERR_NULL, "every weight pointer except b_qkv must be set");
+    cc_status st = check_kv(c, kv);
+    if (st != CC_OK) return st;
+    st = check_rows(c, M);
+    if (st != CC_OK) return st;
+    if (M > kv->N) return fail(c, CC_ERR_SHAPE, "M exceeds the number of cache slots");
+    if (rows < 1 || (!gather_idx && rows < M)) return fail(c, CC_ERR_SHAPE, "hidden has fewer rows than M");
+    if (M == 0) return CC_OK;
+    if (flags & CC_FLAG_CHECK_IDX) {
+        st = check_idx_sync(c, idx, M, kv->N, 1, "idx");
+        if (st != CC_OK) return st;
+        if (gather_idx) {
+            int hi = rows > 0x7fffffff ? 0x7fffffff : (int)rows;
+            st = check_idx_sync(c, gather_idx, M, hi, 0, "gather_idx");
+            if (st != CC_OK) return st;
+        }
+    }
+    st = cc_step_gather_rmsnorm(c, hidden, rows, gather_idx, M, w->w_in_norm, c->xn);
+    if (st != CC_OK) return st;
+    st = cc_step_qkv_rope_scatter(c, c->xn, M, idx, w->w_qkv, w->b_qkv, kv, c->q, 0);
+    if (st != CC_OK) return st;
+    st = cc_step_sparse_attention(c, c->q, M, idx, kv, c->o, 0);
+    if (st != CC_OK) return st;
+    st = cc_step_oproj_residual(c, c->o, M, w->w_o, hidden, rows, gather_idx, c->y);
+    if (st != CC_OK) return st;
+    return cc_step_mlp(c, c->y, M, w->w_post_norm, w->w_gate, w->w_up, w->w_down, out);
+}
+
+cc_status cc_profile_enable(cc_ctx* c, int32_t on) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    c->prof = on != 0;
+    return CC_OK;
+}
+
+cc_status cc_profile_read(cc_ctx* c, float* ms, int32_t* count) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!ms || !count) return fail(c, CC_ERR_NULL, "ms and count must not be NULL");
+    CC_HIP(c, hipStreamSynchronize(c->stream));
+    for (auto& p : c->used) {
+        float t = 0.0f;
+        if (hipEventElapsedTime(&t, p.a, p.b) == hipSuccess) {
+            c->prof_ms[p.kind] += t;
+            c->prof_n[p.kind] += 1;
+        }
+        c->pool.push_back(p);
+    }
+    c->used.clear();
+    for (int i = 0; i < CC_K_COUNT; ++i) {
+        ms[i] = c->prof_ms[i];
+        count[i] = c->prof_n[i];
+        c->prof_ms[i] = 0.0f;
+        c->prof_n[i] = 0;
+    }
+    return CC_OK;
+}
+
+}  // extern "C"

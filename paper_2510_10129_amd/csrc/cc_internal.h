@@ -1,0 +1,80 @@
+// Internal declarations shared by the HIP translation units of the library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "cacheclip.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct cc_event_pair {
+    hipEvent_t a, b;
+    int kind;
+};
+
+struct cc_ctx {
+    cc_model_desc m;
+    hipStream_t stream;
+    int device;
+    std::string err;
+
+    // workspace (device)
+    float2* rope;      // [N_cap][d_h/2] (cos, sin)
+    bf16_t* xn;        // [M_cap][d]          normalised layer input
+    bf16_t* q;         // [M_cap][H_q*d_h]    rotated queries
+    bf16_t* o;         // [M_cap][H_q*d_h]    attention output
+    float* y;          // [M_cap][d]          residual stream after attention
+    bf16_t* mn;        // [M_cap][d]          normalised MLP input
+    bf16_t* act;       // [M_cap][f]          silu(gate)*up
+    float* score;      // [T_cap]
+    int32_t* n_sel;    // [1]
+    int32_t* flag;     // [1] idx check result
+    int32_t* pinned;   // host pinned [2]
+
+    // profiling
+    bool prof;
+    std::vector<cc_event_pair> used;
+    std::vector<cc_event_pair> pool;
+    float prof_ms[CC_K_COUNT];
+    int32_t prof_n[CC_K_COUNT];
+};
+
+// Brackets one kernel launch with events when profiling is on.
+struct cc_prof_scope {
+    cc_ctx* c;
+    cc_event_pair p;
+    bool on;
+    cc_prof_scope(cc_ctx* ctx, int kind);
+    ~cc_prof_scope();
+};
+
+// ---- kernel launchers (each only enqueues on `s`) ----
+void cc_launch_rope_table(float2* table, int n_pos, int d_h, double base, hipStream_t s);
+void cc_launch_colsum(const float* attn, int Q_a, int T, int64_t ld, float* score, hipStream_t s);
+void cc_launch_select(const float* score, int T, int k, int window, int tau, int grouping,
+                      int idx_offset, int n_tail, int32_t* idx_out, int32_t* n_out, hipStream_t s);
+void cc_launch_check_idx(const int32_t* idx, int M, int lo, int hi, int strict, int32_t* flag,
+                         hipStream_t s);
+void cc_launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* gather_idx, int M, int d,
+                              const bf16_t* w, float eps, bf16_t* xn, hipStream_t s);
+void cc_launch_rmsnorm_f32(const float* y, int M, int d, const bf16_t* w, float eps, bf16_t* out,
+                           hipStream_t s);
+void cc_launch_qkv(const bf16_t* xn, int M, const int32_t* idx, const bf16_t* w_qkv,
+                   const bf16_t* b_qkv, const cc_model_desc& m, const float2* rope,
+                   const cc_kv_layer& kv, bf16_t* q_out, hipStream_t s);
+void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_model_desc& m,
+                         const cc_kv_layer& kv, bf16_t* o, hipStream_t s);
+void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hidden,
+                     const int32_t* gather_idx, const cc_model_desc& m, float* y, hipStream_t s);
+void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16_t* w_up,
+                       const cc_model_desc& m, bf16_t* act, hipStream_t s);
+void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float* y,
+                    const cc_model_desc& m, bf16_t* out, hipStream_t s);

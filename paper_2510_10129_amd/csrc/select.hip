@@ -1,0 +1,268 @@
+// Token selection on the device: importance scores, top-k candidates with
+// lowest-index tie-break, sliding-window grouping and compaction
+// (Sections 4.2 and 4.3 of the paper).
+#include "cc_internal.h"
+
+// ----------------------------------------------------------------------------
+// Importance score per chunk token: sum of the query->chunk attention block
+// over its query rows (Section 4.2).  One lane owns one column and adds the
+// rows in ascending order with a single fp32 accumulator, so the result is
+// the same bit pattern on every run and on any host that adds in that order.
+// Loads of 16 rows are issued together; a wave reads 256 contiguous bytes per
+// row.
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void colsum_kernel(const float* __restrict__ attn, int Q_a, int T,
+                                                    int64_t ld, float* __restrict__ score) {
+    int t = blockIdx.x * 64 + threadIdx.x;
+    if (t >= T) return;
+    const float* p = attn + t;
+    float acc = 0.0f;
+    int q = 0;
+    for (; q + 16 <= Q_a; q += 16) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = __builtin_nontemporal_load(p + (int64_t)(q + u) * ld);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc = acc + v[u];
+    }
+    for (; q < Q_a; ++q) acc = acc + p[(int64_t)q * ld];
+    score[t] = acc;
+}
+
+void cc_launch_colsum(const float* attn, int Q_a, int T, int64_t ld, float* score, hipStream_t s) {
+    hipLaunchKernelGGL(colsum_kernel, dim3((T + 63) / 64), dim3(64), 0, s, attn, Q_a, T, ld, score);
+}
+
+// ----------------------------------------------------------------------------
+// Top-k + grouping + compaction in one workgroup of 16 waves.
+//
+// Scores become order-preserving 32-bit keys; the k-th largest key is found by
+// a most-significant-digit-first radix search (4 passes of 8 bits, wave-level
+// aggregated histogram updates); ties at the threshold are ranked by index
+// with wave ballots so that the lowest indices win.  Candidates, passing
+// window starts and chosen tokens are bitmaps in LDS: a window test is a
+// popcount over the words the window spans, and the final compaction is one
+// scan over per-word popcounts.
+// ----------------------------------------------------------------------------
+#define SEL_THREADS 1024
+#define SEL_WAVES 16
+#define SEL_TCAP 131072
+#define SEL_WORDS (SEL_TCAP / 64 + 20)   // bitmap words incl. zero padding past T + window
+
+__device__ __forceinline__ uint32_t score_key(float s) {
+    uint32_t u = __float_as_uint(s + 0.0f);   // -0 -> +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// popcount of bits [b0, b1) of a zero-padded bitmap
+__device__ __forceinline__ int window_popc(const uint64_t* bm, int b0, int b1) {
+    int w0 = b0 >> 6, w1 = (b1 - 1) >> 6;
+    int cnt = 0;
+    for (int wi = w0; wi <= w1; ++wi) {
+        uint64_t word = bm[wi];
+        if (wi == w0) word &= ~0ULL << (b0 & 63);
+        if (wi == w1) {
+            int e = b1 & 63;
+            if (e) word &= (1ULL << e) - 1ULL;
+        }
+        cnt += __popcll(word);
+    }
+    return cnt;
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(
+    const float* __restrict__ score, int T, int k, int window, int tau, int grouping,
+    int idx_offset, int n_tail, int32_t* __restrict__ idx_out, int32_t* __restrict__ n_out) {
+    __shared__ uint64_t cand[SEL_WORDS];
+    __shared__ uint64_t pass[SEL_WORDS];
+    __shared__ uint64_t marked[SEL_WORDS];
+    __shared__ uint32_t word_prefix[SEL_TCAP / 64 + 1];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wave_tot[SEL_WAVES];
+    __shared__ uint32_t sh_prefix, sh_krem, sh_total;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const uint64_t lane_lt = (1ULL << lane) - 1ULL;
+    const int n_words = (T + 63) >> 6;
+
+    for (int i = tid; i < SEL_WORDS; i += SEL_THREADS) {
+        cand[i] = 0;
+        pass[i] = 0;
+        marked[i] = 0;
+    }
+    __syncthreads();
+
+    // ---- threshold key: the k-th largest (0 < k < T) ----
+    uint32_t kth = 0, krem = 0;
+    const bool all = k >= T, none = k <= 0;
+    if (!all && !none) {
+        uint32_t prefix = 0, mask = 0;
+        krem = (uint32_t)k;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            for (int base = 0; base < T; base += SEL_THREADS) {
+                int t = base + tid;
+                bool live = false;
+                uint32_t digit = 0;
+                if (t < T) {
+                    uint32_t key = score_key(score[t]);
+                    live = (key & mask) == prefix;
+                    digit = (key >> shift) & 255u;
+                }
+                // one LDS atomic per distinct digit in the wave
+                uint64_t todo = __ballot(live);
+                while (todo) {
+                    int leader = __ffsll((long long)todo) - 1;
+                    uint32_t dl = __shfl(digit, leader);
+                    uint64_t same = __ballot(live && digit == dl) & todo;
+                    if (lane == leader) atomicAdd(&hist[dl], (uint32_t)__popcll(same));
+                    todo &= ~same;
+                }
+            }
+            __syncthreads();
+            if (tid == 0) {
+                uint32_t cum = 0;
+                int b = 255;
+                for (; b > 0; --b) {
+                    uint32_t h = hist[b];
+                    if (cum + h >= krem) break;
+                    cum += h;
+                }
+                sh_prefix = prefix | ((uint32_t)b << shift);
+                sh_krem = krem - cum;
+            }
+            __syncthreads();
+            prefix = sh_prefix;
+            krem = sh_krem;
+            mask |= 255u << shift;
+        }
+        kth = prefix;
+    }
+
+    // ---- candidate bitmap; equal keys are taken in index order ----
+    uint32_t carry = 0;
+    for (int base = 0; base < T; base += SEL_THREADS) {
+        int t = base + tid;
+        bool gt = false, eq = false;
+        if (t < T) {
+            if (all) {
+                gt = true;
+            } else if (!none) {
+                uint32_t key = score_key(score[t]);
+                gt = key > kth;
+                eq = key == kth;
+            }
+        }
+        uint64_t be = __ballot(eq);
+        if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(be);
+        __syncthreads();
+        uint32_t before = carry, total = 0;
+        for (int w = 0; w < SEL_WAVES; ++w) {
+            uint32_t c = wave_tot[w];
+            if (w < wave) before += c;
+            total += c;
+        }
+        uint32_t rank = before + (uint32_t)__popcll(be & lane_lt);
+        bool is_c = gt || (eq && rank < krem);
+        uint64_t bc = __ballot(is_c);
+        if (lane == 0) cand[(base >> 6) + wave] = bc;
+        carry += total;
+        __syncthreads();
+    }
+
+    // ---- windows that start at a candidate and hold >= tau candidates ----
+    if (grouping) {
+        for (int base = 0; base < T; base += SEL_THREADS) {
+            int t = base + tid;
+            bool ok = false;
+            if (t < T && ((cand[t >> 6] >> (t & 63)) & 1ULL))
+                ok = window_popc(cand, t, t + window) >= tau;   // bits past T are zero
+            uint64_t b = __ballot(ok);
+            if (lane == 0) pass[(base >> 6) + wave] = b;
+        }
+        __syncthreads();
+        // a token is chosen when some passing window covers it
+        for (int base = 0; base < T; base += SEL_THREADS) {
+            int t = base + tid;
+            bool ok = false;
+            if (t < T) {
+                int b0 = t - window + 1;
+                ok = window_popc(pass, b0 < 0 ? 0 : b0, t + 1) > 0;
+            }
+            uint64_t b = __ballot(ok);
+            if (lane == 0) marked[(base >> 6) + wave] = b;
+        }
+    } else {
+        for (int i = tid; i < n_words; i += SEL_THREADS) marked[i] = cand[i];
+    }
+    __syncthreads();
+
+    // ---- exclusive scan of per-word popcounts ----
+    uint32_t run = 0;
+    for (int base = 0; base < n_words; base += SEL_THREADS) {
+        int wi = base + tid;
+        uint32_t c = wi < n_words ? (uint32_t)__popcll(marked[wi]) : 0u;
+        uint32_t inc = c;
+        for (int off = 1; off < 64; off <<= 1) {
+            uint32_t o = __shfl_up(inc, off);
+            if (lane >= off) inc += o;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        uint32_t before = run, total = 0;
+        for (int w = 0; w < SEL_WAVES; ++w) {
+            uint32_t cw = wave_tot[w];
+            if (w < wave) before += cw;
+            total += cw;
+        }
+        if (wi < n_words) word_prefix[wi] = before + inc - c;
+        run += total;
+        __syncthreads();
+    }
+    const uint32_t n_sel = run;
+
+    // ---- compaction: ascending token order by construction ----
+    for (int base = 0; base < T; base += SEL_THREADS) {
+        int t = base + tid;
+        if (t < T) {
+            uint64_t word = marked[t >> 6];
+            if ((word >> (t & 63)) & 1ULL) {
+                uint32_t pos = word_prefix[t >> 6] + (uint32_t)__popcll(word & ((1ULL << (t & 63)) - 1ULL));
+                idx_out[pos] = idx_offset + t;
+            }
+        }
+    }
+    for (int j = tid; j < n_tail; j += SEL_THREADS) idx_out[n_sel + j] = idx_offset + T + j;
+    if (tid == 0) *n_out = (int32_t)n_sel + n_tail;
+    (void)sh_total;
+}
+
+void cc_launch_select(const float* score, int T, int k, int window, int tau, int grouping,
+                      int idx_offset, int n_tail, int32_t* idx_out, int32_t* n_out, hipStream_t s) {
+    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(SEL_THREADS), 0, s, score, T, k, window, tau,
+                       grouping, idx_offset, n_tail, idx_out, n_out);
+}
+
+// ----------------------------------------------------------------------------
+// idx check: strictly ascending (or merely in range when strict == 0), each in
+// [lo, hi).  flag receives the number of violations.
+// ----------------------------------------------------------------------------
+__global__ void check_idx_kernel(const int32_t* __restrict__ idx, int M, int lo, int hi, int strict,
+                                 int32_t* __restrict__ flag) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    int v = idx[i];
+    bool bad = v < lo || v >= hi;
+    if (strict && i > 0 && idx[i - 1] >= v) bad = true;
+    if (bad) atomicAdd(flag, 1);
+}
+
+void cc_launch_check_idx(const int32_t* idx, int M, int lo, int hi, int strict, int32_t* flag,
+                         hipStream_t s) {
+    if (M <= 0) return;
+    hipLaunchKernelGGL(check_idx_kernel, dim3((M + 255) / 256), dim3(256), 0, s, idx, M, lo, hi,
+                       strict, flag);
+}

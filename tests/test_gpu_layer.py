@@ -1,0 +1,312 @@
+"""GPU parity of cc_recompute_layer and its stages against the oracle.
+
+Tolerances (bf16 inputs, fp32 accumulation, fp64 oracle): layer outputs and
+updated K/V rows max abs <= 2e-2 and mean abs <= 2e-3; scatter positions and
+untouched cache rows bit-exact.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_10129_amd as cc
+from paper_2510_10129_amd import _lib
+from oracle import bf16 as obf
+from oracle import fixture, layer
+from workloads import CONFIGS, ModelShape, gen
+
+from _gpu_util import DEV, bits_f64, dev_bf16, dev_i32, dev_weights, err_stats, host_bits
+
+pytestmark = pytest.mark.gpu
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+
+
+def _ctx(model, N, M):
+    return cc.Context.for_model(model, N_cap=N, M_cap=max(M, 1), T_cap=1024)
+
+
+def _x_bits(n, d, seed, scale=1.0):
+    r = np.random.default_rng(seed)
+    return gen.f32_to_bf16_bits((r.standard_normal((n, d)) * scale).astype(np.float32))
+
+
+def _run_layer(model, xg_bits, gather, Ks, Vs, idx, w, rows=None, flags=_lib.FLAG_CHECK_IDX):
+    """Runs the HIP layer and the oracle on the same inputs; returns both."""
+    N, M = Ks.shape[0], len(idx)
+    ctx = _ctx(model, N, M)
+    Kd, Vd = dev_bf16(Ks), dev_bf16(Vs)
+    hid = dev_bf16(xg_bits)
+    out = torch.full((max(M, 1), model.d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ctx.recompute_layer(hid, None if gather is None else dev_i32(gather), cc.KVLayer(Kd, Vd),
+                        dev_i32(idx), M, dev_weights(w), out, flags)
+    torch.cuda.synchronize()
+    ref = layer.recompute_layer(xg_bits, gather, Ks, Vs, idx, w, model, rows=rows)
+    got = dict(out=host_bits(out)[:M], K=host_bits(Kd), V=host_bits(Vd))
+    ctx.close()
+    return got, ref
+
+
+def _assert_layer(got, ref, Ks, Vs, idx, tag=""):
+    idx = np.asarray(idx)
+    N = Ks.shape[0]
+    untouched = np.setdiff1d(np.arange(N), idx)
+    # scatter positions: every row outside idx keeps its bits
+    assert np.array_equal(got["K"][untouched], Ks[untouched]), tag
+    assert np.array_equal(got["V"][untouched], Vs[untouched]), tag
+    # fresh rows against the oracle's unrounded values
+    for name, fresh in (("K", ref.k_new), ("V", ref.v_new)):
+        mx, mn = err_stats(bits_f64(got[name][idx]), fresh)
+        assert mx <= MAX_ABS and mn <= MEAN_ABS, (tag, name, mx, mn)
+        # and nearly always the same bf16 code as the oracle's own rounding
+        same = (got[name][idx] == (ref.K_bits if name == "K" else ref.V_bits)[idx]).mean()
+        assert same > 0.6, (tag, name, same)
+    mx, mn = err_stats(bits_f64(got["out"][ref.rows]), ref.out)
+    print(f"{tag}: out max {mx:.2e} mean {mn:.2e}")
+    assert np.isfinite(bits_f64(got["out"])).all(), tag
+    assert mx <= MAX_ABS and mn <= MEAN_ABS, (tag, mx, mn)
+
+
+def test_tiny_config_full_parity():
+    wl = CONFIGS["C1"]
+    w = gen.layer_weights(wl.model, 0, wl.seed)
+    xl, xg = gen.hidden_pair(wl)
+    Ks, Vs = fixture.stale_cache_one_layer(xl, w, wl.model)
+    Ks[wl.P + wl.T:], Vs[wl.P + wl.T:] = 0, 0
+    from oracle import select as osel
+    idx = osel.select(gen.aux_attention(wl), 2000, wl.window, wl.tau, True, wl.P, wl.Q)
+    got, ref = _run_layer(wl.model, xg, idx, Ks, Vs, idx, w)
+    _assert_layer(got, ref, Ks, Vs, idx, "C1")
+    # the stale rows that were recomputed really changed
+    assert (got["K"][idx[:-wl.Q]] != Ks[idx[:-wl.Q]]).mean() > 0.5
+
+
+SHAPES = [
+    # (model, N, idx builder) - head dims, group sizes, bias, ragged sizes
+    (ModelShape(128, 4, 2, 64, 192, 1e4, 1e-5, False, 1), 300, "runs"),
+    (ModelShape(256, 2, 2, 128, 320, 5e5, 1e-5, True, 1), 257, "all"),
+    (ModelShape(448, 7, 1, 64, 128, 1e6, 1e-6, True, 1), 200, "runs"),
+    (ModelShape(1024, 8, 1, 128, 256, 5e5, 1e-5, False, 1), 333, "tail"),
+    (ModelShape(192, 3, 1, 64, 64, 1e4, 1e-5, False, 1), 131, "single"),
+    (ModelShape(2048, 32, 1, 64, 128, 1e4, 1e-5, False, 1), 100, "runs"),
+]
+
+
+@pytest.mark.parametrize("model,N,kind", SHAPES)
+def test_shapes_and_edge_cases(model, N, kind):
+    rng = np.random.default_rng(N)
+    w = gen.layer_weights(model, 0, seed=N)
+    # bigger projections than the default recipe: peaked attention, every key matters
+    for k in ("w_qkv",):
+        w[k] = gen.f32_to_bf16_bits(gen.bf16_to_f32(w[k]) * 3.0)
+    xl, xg = _x_bits(N, model.d, 1), _x_bits(N, model.d, 2)
+    Ks, Vs = fixture.stale_cache_one_layer(xl, w, model)
+    if kind == "all":
+        idx = np.arange(N)
+    elif kind == "tail":
+        idx = np.arange(N - 9, N)
+    elif kind == "single":
+        idx = np.array([77])
+    else:
+        marks = np.zeros(N, bool)
+        for s in rng.integers(1, N - 10, size=N // 12):
+            marks[s:s + int(rng.integers(1, 9))] = True
+        marks[N - 5:] = True
+        idx = np.nonzero(marks)[0]
+    got, ref = _run_layer(model, xg, idx, Ks, Vs, idx, w)
+    _assert_layer(got, ref, Ks, Vs, idx, f"{kind} d={model.d} g={model.g} d_h={model.d_h}")
+
+
+def test_compact_hidden_and_zero_rows():
+    model = SHAPES[0][0]
+    N = 150
+    w = gen.layer_weights(model, 0, seed=9)
+    xl, xg = _x_bits(N, model.d, 3), _x_bits(N, model.d, 4)
+    Ks, Vs = fixture.stale_cache_one_layer(xl, w, model)
+    idx = np.array([3, 4, 5, 60, 61, 62, 63, 149])
+    got, ref = _run_layer(model, xg[idx], None, Ks, Vs, idx, w)      # hidden already compact
+    _assert_layer(got, ref, Ks, Vs, idx, "compact")
+    # M = 0: nothing changes, no error
+    ctx = _ctx(model, N, 4)
+    Kd, Vd = dev_bf16(Ks), dev_bf16(Vs)
+    out = torch.zeros((1, model.d), dtype=torch.bfloat16, device=DEV)
+    ctx.recompute_layer(dev_bf16(xg), None, cc.KVLayer(Kd, Vd), dev_i32([0]), 0, dev_weights(w), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(Kd), Ks) and np.array_equal(host_bits(Vd), Vs)
+    ctx.close()
+
+
+def test_strided_cache_view():
+    """K and V as slices of one [N, 2, H_kv, d_h] allocation (token stride 2*H_kv*d_h)."""
+    model = SHAPES[0][0]
+    N = 120
+    w = gen.layer_weights(model, 0, seed=11)
+    xl, xg = _x_bits(N, model.d, 5), _x_bits(N, model.d, 6)
+    Ks, Vs = fixture.stale_cache_one_layer(xl, w, model)
+    idx = np.array([10, 11, 12, 13, 50, 51, 118, 119])
+    both = torch.stack([dev_bf16(Ks), dev_bf16(Vs)], dim=1).contiguous()
+    Kd, Vd = both[:, 0], both[:, 1]
+    ctx = _ctx(model, N, len(idx))
+    out = torch.empty((len(idx), model.d), dtype=torch.bfloat16, device=DEV)
+    ctx.recompute_layer(dev_bf16(xg), dev_i32(idx), cc.KVLayer(Kd, Vd), dev_i32(idx), len(idx),
+                        dev_weights(w), out, _lib.FLAG_CHECK_IDX)
+    torch.cuda.synchronize()
+    ref = layer.recompute_layer(xg, idx, Ks, Vs, idx, w, model)
+    got = dict(out=host_bits(out), K=host_bits(Kd), V=host_bits(Vd))
+    _assert_layer(got, ref, Ks, Vs, idx, "strided")
+    ctx.close()
+
+
+def test_idx_check_and_argument_errors():
+    model = SHAPES[0][0]
+    N = 64
+    w = gen.layer_weights(model, 0, seed=12)
+    x = _x_bits(N, model.d, 7)
+    Ks, Vs = fixture.stale_cache_one_layer(x, w, model)
+    ctx = _ctx(model, N, 8)
+    Kd, Vd = dev_bf16(Ks), dev_bf16(Vs)
+    out = torch.empty((8, model.d), dtype=torch.bfloat16, device=DEV)
+    args = lambda idx, M: (dev_bf16(x), dev_i32(idx), cc.KVLayer(Kd, Vd), dev_i32(idx), M, dev_weights(w), out)
+    for bad in ([5, 5, 6], [7, 6, 8], [1, 2, 64], [-1, 2, 3]):
+        with pytest.raises(cc.CacheClipError) as e:
+            ctx.recompute_layer(*args(bad, 3), _lib.FLAG_CHECK_IDX)
+        assert e.value.status == _lib.CC_ERR_IDX
+    with pytest.raises(cc.CacheClipError) as e:
+        ctx.recompute_layer(*args(list(range(9)), 9))
+    assert e.value.status == _lib.CC_ERR_WORKSPACE
+    with pytest.raises(cc.CacheClipError) as e:
+        ctx.recompute_layer(*args([1], -1))
+    assert e.value.status == _lib.CC_ERR_SHAPE
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(Kd), Ks)          # failed calls wrote nothing
+    ctx.close()
+
+
+# ------------------------------------------------------------ single stages
+def test_stage_attention_peaked_random():
+    """The attention kernel alone, on q/K/V drawn directly so that the softmax is
+    sharply peaked and the causal boundary matters."""
+    for (H_q, H_kv, d_h, N, seed) in ((8, 2, 128, 700, 0), (4, 4, 64, 333, 1), (7, 1, 128, 190, 2),
+                                      (16, 2, 64, 1000, 3)):
+        rng = np.random.default_rng(seed)
+        model = ModelShape(H_q * d_h, H_q, H_kv, d_h, 64, 1e4, 1e-5, False, 1)
+        marks = rng.random(N) < 0.3
+        marks[0] = True
+        marks[N - 1] = True
+        idx = np.nonzero(marks)[0]
+        M = len(idx)
+        qb = gen.f32_to_bf16_bits((rng.standard_normal((M, H_q, d_h)) * 2.5).astype(np.float32))
+        Kb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+        Vb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+        ctx = _ctx(model, N, M)
+        o = torch.empty((M, H_q * d_h), dtype=torch.bfloat16, device=DEV)
+        ctx.step_sparse_attention(dev_bf16(qb).view(M, -1), M, dev_i32(idx),
+                                  cc.KVLayer(dev_bf16(Kb), dev_bf16(Vb)), o, _lib.FLAG_CHECK_IDX)
+        torch.cuda.synchronize()
+        qf, Kf, Vf = obf.bits_to_f64(qb), obf.bits_to_f64(Kb), obf.bits_to_f64(Vb)
+        ref = np.stack([layer.attend_row(qf[i], Kf, Vf, int(idx[i]), H_q // H_kv)[0].reshape(-1)
+                        for i in range(M)])
+        mx, mn = err_stats(bits_f64(host_bits(o)), ref)
+        print(f"attention H_q={H_q} H_kv={H_kv} d_h={d_h}: max {mx:.2e} mean {mn:.2e}")
+        assert mx <= MAX_ABS and mn <= MEAN_ABS
+        ctx.close()
+
+
+def test_stage_projections_against_oracle_pieces():
+    model = ModelShape(512, 8, 2, 64, 768, 1e4, 1e-5, True, 1)
+    N, M = 500, 203
+    rng = np.random.default_rng(5)
+    w = gen.layer_weights(model, 0, seed=21)
+    xb = _x_bits(N, model.d, 8)
+    idx = np.sort(rng.choice(N, size=M, replace=False))
+    ctx = _ctx(model, N, M)
+    dw = dev_weights(w)
+    hid = dev_bf16(xb)
+    # R1 gather + RMSNorm
+    xn = torch.empty((M, model.d), dtype=torch.bfloat16, device=DEV)
+    ctx.step_gather_rmsnorm(hid, dev_i32(idx), M, dw.w_in_norm, xn)
+    xf = obf.bits_to_f64(xb[idx])
+    n_ref = layer.rmsnorm(xf, obf.bits_to_f64(w["w_in_norm"]), model.rms_eps)
+    mx, _ = err_stats(bits_f64(host_bits(xn)), n_ref)
+    assert mx <= 2.0 ** -8 * np.abs(n_ref).max()
+    # R2-R4 QKV + RoPE + scatter
+    Ks = np.zeros((N, model.H_kv, model.d_h), np.uint16)
+    Kd, Vd = dev_bf16(Ks), dev_bf16(Ks)
+    q = torch.empty((M, model.H_q * model.d_h), dtype=torch.bfloat16, device=DEV)
+    ctx.step_qkv_rope_scatter(xn, M, dev_i32(idx), dw.w_qkv, dw.b_qkv, cc.KVLayer(Kd, Vd), q,
+                              _lib.FLAG_CHECK_IDX)
+    q_ref, k_ref, v_ref = layer.qkv_rows(xf, w, model, idx)
+    for got, ref in ((host_bits(q).reshape(M, model.H_q, -1), q_ref),
+                     (host_bits(Kd)[idx], k_ref), (host_bits(Vd)[idx], v_ref)):
+        mx, mn = err_stats(bits_f64(got), ref)
+        assert mx <= MAX_ABS and mn <= MEAN_ABS, (mx, mn)
+    rest = np.setdiff1d(np.arange(N), idx)
+    assert not host_bits(Kd)[rest].any() and not host_bits(Vd)[rest].any()
+    # R6 O projection + residual
+    ob = _x_bits(M, model.H_q * model.d_h, 9, 0.5)
+    y = torch.empty((M, model.d), dtype=torch.float32, device=DEV)
+    ctx.step_oproj_residual(dev_bf16(ob), M, dw.w_o, hid, dev_i32(idx), y)
+    y_ref = xf + obf.bits_to_f64(ob) @ obf.bits_to_f64(w["w_o"]).T
+    mx, mn = err_stats(y.cpu().numpy().astype(np.float64), y_ref)
+    assert mx <= 1e-4, mx                      # fp32 accumulation of exact bf16 products
+    # R7 MLP
+    out = torch.empty((M, model.d), dtype=torch.bfloat16, device=DEV)
+    ctx.step_mlp(y, M, dw.w_post_norm, dw.w_gate, dw.w_up, dw.w_down, out)
+    torch.cuda.synchronize()
+    yf = y.cpu().numpy().astype(np.float64)
+    m = layer.rmsnorm(yf, obf.bits_to_f64(w["w_post_norm"]), model.rms_eps)
+    z = yf + (layer.silu(m @ obf.bits_to_f64(w["w_gate"]).T) * (m @ obf.bits_to_f64(w["w_up"]).T)) \
+        @ obf.bits_to_f64(w["w_down"]).T
+    mx, mn = err_stats(bits_f64(host_bits(out)), z)
+    assert mx <= MAX_ABS and mn <= MEAN_ABS, (mx, mn)
+    ctx.close()
+
+
+# ------------------------------------------------------------ stack and full-size shapes
+def test_two_layer_stack_with_real_stale_caches():
+    wl = CONFIGS["C1x2"]
+    model = wl.model
+    ws = [gen.layer_weights(model, l, wl.seed) for l in range(2)]
+    xl, _ = gen.hidden_pair(wl)
+    Ks, Vs = fixture.stale_caches(xl, wl.P, wl.chunk_lens, wl.Q, ws, model)
+    idx = gen.exact_ratio_idx(wl, 2000)
+    M = len(idx)
+    ref = fixture.selective_prefill(xl, Ks, Vs, idx, ws, model)
+    ctx = _ctx(model, wl.N, M)
+    h, gidx = dev_bf16(xl), dev_i32(idx)
+    didx = dev_i32(idx)
+    for l in range(2):
+        Kd, Vd = dev_bf16(Ks[l]), dev_bf16(Vs[l])
+        out = torch.empty((M, model.d), dtype=torch.bfloat16, device=DEV)
+        ctx.recompute_layer(h, gidx, cc.KVLayer(Kd, Vd), didx, M, dev_weights(ws[l]), out,
+                            _lib.FLAG_CHECK_IDX)
+        torch.cuda.synchronize()
+        got = dict(out=host_bits(out), K=host_bits(Kd), V=host_bits(Vd))
+        _assert_layer(got, ref[l], Ks[l], Vs[l], idx, f"stack layer {l}")
+        h, gidx = out, None
+    ctx.close()
+
+
+def _sampled_layer_case(name, bp, n_rows, seed):
+    wl = CONFIGS[name]
+    model = replace(wl.model, n_layers=1)
+    w = gen.layer_weights(model, 0, wl.seed)
+    xl, xg = gen.hidden_pair(wl)
+    Ks, Vs = fixture.stale_cache_one_layer(xl, w, model)
+    Ks[wl.P + wl.T:], Vs[wl.P + wl.T:] = 0, 0
+    idx = gen.exact_ratio_idx(wl, bp)
+    M = len(idx)
+    rows = np.sort(np.random.default_rng(seed).choice(M, size=n_rows, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    got, ref = _run_layer(model, xg, idx, Ks, Vs, idx, w, rows=rows)
+    _assert_layer(got, ref, Ks, Vs, idx, f"{name}@{bp // 100}% M={M}")
+
+
+@pytest.mark.parametrize("bp", [1000, 4000])
+def test_llama8b_layer_4k_sampled_rows(bp):
+    _sampled_layer_case("C2", bp, 24, bp)
+
+
+def test_llama8b_layer_16k_bench_shape_sampled_rows():
+    """The shape and launch configuration bench.py times (one layer of it)."""
+    _sampled_layer_case("C3", 2000, 16, 7)
