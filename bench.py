@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the selective KV-recompute prefill path on one MI355X.
+
+One step = one request through the whole hot path: token selection on the
+auxiliary attention block (column sums, top-k, grouping) followed by the
+selective recompute of every layer of the stack.  Inputs are synthetic, seeded
+and already resident in HBM when the timed region starts.
+
+Prints ONE JSON line.  `value` is the metric's "recomputed tok/s": the M rows a
+request recomputes divided by the mean time one layer takes (step time / number
+of layers, selection included); `ms_per_layer` is printed next to it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--recomp-bp", type=int, default=2000)
+    ap.add_argument("--layers", type=int, default=0, help="override the stack depth (0 = the workload's)")
+    ap.add_argument("--exact-idx", action="store_true",
+                    help="time the layers on a hand-built set of exactly recomp%% tokens instead of select's output")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def algorithmic_work(model, idx_host, N, Q_a, T):
+    """FLOPs / bytes the method itself needs per launch of each kernel."""
+    M = len(idx_host)
+    d, f, dh, Hq, Hkv = model.d, model.f, model.d_h, model.H_q, model.H_kv
+    nqkv = (Hq + 2 * Hkv) * dh
+    keys = int((idx_host.astype("int64") + 1).sum())
+    return {
+        "colsum": ("hbm", Q_a * T * 4 + T * 4),
+        "select": ("hbm", T * 4 * 5 + M * 4),
+        "gather_norm": ("hbm", M * d * 2 * 2),
+        "qkv": ("mfma", 2 * M * d * nqkv),
+        "attn": ("mfma", 4 * dh * Hq * keys),
+        "oproj": ("mfma", 2 * M * Hq * dh * d),
+        "post_norm": ("hbm", M * d * (4 + 2)),
+        "gate_up": ("mfma", 4 * M * d * f),
+        "down": ("mfma", 2 * M * f * d),
+    }
+
+
+def cpu_baseline(wl, model, recomp_bp, n_rows=6):
+    """The oracle as it stands, on the host cores: selection in full; one layer with
+    the K/V update (steps 1-4) for all M rows and attention + the rest of the layer
+    (steps 5-7) for a few sampled rows, scaled to M rows."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import layer as olayer
+    from oracle import select as osel
+    from workloads import gen
+
+    t0 = time.perf_counter()
+    A = gen.aux_attention(wl)
+    t_gen = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    idx = osel.select(A, recomp_bp, wl.window, wl.tau, True, wl.P, wl.Q)
+    t_sel = time.perf_counter() - t0
+    M = len(idx)
+    w = gen.layer_weights(model, 0, wl.seed)
+    _, xg = gen.hidden_pair(wl)
+    Kb, Vb = gen.random_cache(wl)
+    # the all-row part (rows=[]) is timed in full; the per-row part is timed at two
+    # sample sizes so that the fixed cost (widening the weights) is not scaled with M
+    rng = np.random.default_rng(0)
+    n1, n2 = min(n_rows, M), min(4 * n_rows, M)
+    rows1 = np.sort(rng.choice(M, size=n1, replace=False))
+    rows2 = np.sort(rng.choice(M, size=n2, replace=False))
+    t0 = time.perf_counter()
+    olayer.recompute_layer(xg, idx, Kb, Vb, idx, w, model, rows=[])
+    t_kv = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    olayer.recompute_layer(xg, idx, Kb, Vb, idx, w, model, rows=rows1)
+    t1 = time.perf_counter() - t0 - t_kv
+    t0 = time.perf_counter()
+    olayer.recompute_layer(xg, idx, Kb, Vb, idx, w, model, rows=rows2)
+    t2 = time.perf_counter() - t0 - t_kv
+    per_row = max((t2 - t1) / max(n2 - n1, 1), 1e-9)
+    fixed = max(t1 - n1 * per_row, 0.0)
+    layer_s = t_kv + fixed + per_row * M
+    rows, t_rows = rows2, t2
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {
+        "value": M / layer_s, "unit": "recomputed tok/s", "cores": threads, "kind": "oracle",
+        "ms_per_layer": layer_s * 1e3, "select_ms": t_sel * 1e3, "extrapolated": True,
+        "sample": (f"numpy fp64 oracle, one layer of {wl.name}: QKV+RoPE+scatter for all {M} rows "
+                   f"({t_kv:.1f} s) + attention/O/MLP for {len(rows)} sampled rows ({t_rows:.1f} s) "
+                   f"and {n1} rows, per-row slope scaled to {M} rows; selection in full ({t_sel * 1e3:.0f} ms)"),
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2510_10129_amd as cc
+    from workloads import CONFIGS, gen, gen_device
+    from dataclasses import replace
+
+    wl = CONFIGS[a.workload]
+    model = wl.model
+    L = a.layers if a.layers > 0 else model.n_layers
+    if L != model.n_layers:
+        model = replace(model, n_layers=L)
+        wl = replace(wl, model=model)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+
+    # ---- inputs, resident in HBM ----
+    A = torch.from_numpy(gen.aux_attention(wl)).to(dev)
+    X = gen_device.hidden(wl, dev)
+    weights = [cc.LayerWeights(**gen_device.layer_weights(model, l, wl.seed, dev)) for l in range(L)]
+    caches = [cc.KVLayer(*gen_device.cache(wl, l, dev)) for l in range(L)]
+    ctx = cc.Context.for_model(model, N_cap=wl.N, M_cap=wl.N, T_cap=wl.T)
+    idx = torch.empty(wl.T + wl.Q, dtype=torch.int32, device=dev)
+    n_out = torch.empty(1, dtype=torch.int32, device=dev)
+    bufs = [torch.empty((wl.N, model.d), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    exact = torch.from_numpy(gen.exact_ratio_idx(wl, a.recomp_bp)).to(dev) if a.exact_idx else None
+
+    def step():
+        sel_idx, M = ctx.select(A, a.recomp_bp, wl.window, wl.tau, 0, wl.P, wl.Q, idx_out=idx, n_out=n_out)
+        if exact is not None:
+            sel_idx, M = exact, exact.numel()
+        h, g = X, sel_idx
+        for l in range(L):
+            out = bufs[l & 1]
+            ctx.recompute_layer(h, g, caches[l], sel_idx, M, weights[l], out, 0)
+            h, g = out, None
+        return M
+
+    for _ in range(a.warmup):
+        M = step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        M = step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+
+    # ---- same steps again with the library's HIP events around every kernel ----
+    ctx.profile_enable(True)
+    ctx.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_ev = (time.perf_counter() - t0) / a.steps
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+
+    idx_host = (exact if exact is not None else idx)[:M].cpu().numpy()
+    work = algorithmic_work(model, idx_host, wl.N, wl.Q_a, wl.T)
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        avg_ms = ms / cnt
+        bound, amount = work[name]
+        if bound == "mfma":
+            ach = amount / (avg_ms * 1e-3) / 1e12
+            kernels[name] = {"avg_ms": round(avg_ms, 5), "launches_per_step": cnt // a.steps, "bound": bound,
+                             "achieved_TFLOPs": round(ach, 2), "frac": round(ach / PEAK_BF16_TFLOPS, 4)}
+        else:
+            ach = amount / (avg_ms * 1e-3) / 1e9
+            kernels[name] = {"avg_ms": round(avg_ms, 5), "launches_per_step": cnt // a.steps, "bound": bound,
+                             "achieved_GBs": round(ach, 1), "frac": round(ach / PEAK_HBM_GBS, 4)}
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_per_step"])
+    kd = kernels[dom]
+    roofline = {
+        "kernel": dom, "bound": kd["bound"],
+        "achieved": kd.get("achieved_TFLOPs", kd.get("achieved_GBs")),
+        "peak": PEAK_BF16_TFLOPS if kd["bound"] == "mfma" else PEAK_HBM_GBS,
+        "unit": "TFLOP/s" if kd["bound"] == "mfma" else "GB/s",
+        "frac": kd["frac"], "traffic": None, "avg_ms": kd["avg_ms"],
+    }
+    layer_flops = sum(v for k, (b, v) in work.items() if b == "mfma")
+    ms_per_layer = dt * 1e3 / L
+    res = {
+        "metric": "selective-recompute prefill recomputed tok/s @recomp=20% (M rows / ms per layer)",
+        "value": M / (ms_per_layer * 1e-3), "unit": "tok/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": dt * 1e3, "ms_per_layer": ms_per_layer,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {L}-layer d={model.d} {model.H_q}q/{model.H_kv}kv d_h={model.d_h} "
+                               f"f={model.f}; P={wl.P} + {len(wl.chunk_lens)} chunks (T={wl.T}) + Q={wl.Q}, N={wl.N}",
+                   "recomp_bp": a.recomp_bp, "window": wl.window, "tau": wl.tau, "layers": L,
+                   "M": int(M), "M_sel_over_T": round((M - wl.Q) / wl.T, 4),
+                   "idx": "exact-ratio runs" if a.exact_idx else "select output"},
+        "layer_algorithmic_TFLOP": round(layer_flops / 1e12, 4),
+        "layer_frac_of_bf16_peak": round(layer_flops / (ms_per_layer * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "ms_per_step_with_events": dt_ev * 1e3,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, model, a.recomp_bp)
+    ctx.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

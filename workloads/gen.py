@@ -88,9 +88,11 @@ def aux_attention(wl: Workload) -> np.ndarray:
     attention, synthesised.  Rows are softmaxes over the T chunk tokens.
 
     spikes   : N(0,1) logits plus 8 spikes of +6 at random columns per row.
-    heavy    : 2*N(0,1) logits plus ~T/256 bumps of +4 shared by all rows over
-               spans of U[4,24] tokens, so that high column sums come in runs
-               (a few tokens carry most of the mass, as the paper observes).
+    heavy    : 2*N(0,1) logits plus T/64 bumps of +4 shared by all rows over
+               spans of U[4,24] tokens (about a fifth of the tokens), so that high
+               column sums come in runs and a recompute ratio of 20 % ends up
+               with roughly 20 % of the tokens after grouping (a few tokens
+               carry most of the mass, as the paper observes).
     boundary : heavy, with the bump starts drawn within +-32 tokens of chunk
                starts (attention-sink-like mass at chunk boundaries).
     """
@@ -103,7 +105,7 @@ def aux_attention(wl: Workload) -> np.ndarray:
             z[q, cols] += 6.0
     else:
         z *= 2.0
-        n_bumps = max(1, T // 256)
+        n_bumps = max(1, T // 64)
         lens = r.integers(4, 25, size=n_bumps)
         if wl.score_kind == "boundary":
             starts_c = np.asarray(wl.chunk_starts)
