@@ -32,7 +32,7 @@ namespace {
 constexpr int BN_KEYS = 64;
 
 template <int D_H>
-__global__ __launch_bounds__(256) void sparse_attn_kernel(
+__global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
     const bf16_t* __restrict__ q, int M, const int32_t* __restrict__ idx, int H_q, int H_kv,
     const bf16_t* __restrict__ Kc, const bf16_t* __restrict__ Vc, int64_t st, int64_t sh, int N,
     bf16_t* __restrict__ o, int n_row_tiles, float scale_log2) {
@@ -66,6 +66,10 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(
     int wave_limit = limit;
     for (int off = 32; off > 0; off >>= 1) wave_limit = max(wave_limit, __shfl_xor(wave_limit, off));
 
+    // wave-wide smallest limit of a valid row: tiles that end at or below it need no mask
+    int wave_min = valid ? limit : 0x7fffffff;
+    for (int off = 32; off > 0; off >>= 1) wave_min = min(wave_min, __shfl_xor(wave_min, off));
+
     // ---- Q fragments (B operand of S^T = K Q^T): lane = query row, 8 d's per k-step ----
     bf16x8 qf[KS];
     {
@@ -81,48 +85,58 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(
         }
     }
 
-    // ---- global -> LDS staging addresses ----
+    // ---- global -> LDS staging: per-lane 32-bit offsets from a wave-uniform tile base ----
     const bf16_t* kbase = Kc + (int64_t)kvh * sh;
     const bf16_t* vbase = Vc + (int64_t)kvh * sh;
-    int k_row[K_CH], k_col[K_CH], k_off[K_CH];
+    const int k_r0 = tid / KCPR, k_c = (tid % KCPR) * 8;      // chunk i: row k_r0 + i*(256/KCPR)
+    const int v_kg0 = tid / LPR, v_d = 2 * (tid % LPR);       // item i: key group v_kg0 + i*(256/LPR)
+    int koff[K_CH], k_lds[K_CH], voff[V_IT];
 #pragma unroll
     for (int i = 0; i < K_CH; ++i) {
-        int c = tid + i * 256, r = c / KCPR, kc = c % KCPR;
-        k_row[i] = r;
-        k_col[i] = kc * 8;
-        k_off[i] = r * D_H + ((kc ^ (r & 7)) << 3);
+        int r = k_r0 + i * (256 / KCPR);
+        koff[i] = r * (int)st + k_c;
+        k_lds[i] = r * D_H + (((k_c >> 3) ^ (r & 7)) << 3);
     }
-    int v_kg[V_IT], v_d0[V_IT];
 #pragma unroll
-    for (int i = 0; i < V_IT; ++i) {
-        int it = tid + i * 256;
-        v_kg[i] = it / LPR;
-        v_d0[i] = 2 * (it % LPR);
-    }
+    for (int i = 0; i < V_IT; ++i) voff[i] = (v_kg0 + i * (256 / LPR)) * 8 * (int)st + v_d;
 
-    uint4 rk[K_CH];
+    u32x4 rk[K_CH];
     uint32_t rv[V_IT][8];
     auto load_tile = [&](int j0) {
+        const bf16_t* kb = kbase + (int64_t)j0 * st;
+        const bf16_t* vb = vbase + (int64_t)j0 * st;
+        if (j0 + BN_KEYS <= N) {
 #pragma unroll
-        for (int i = 0; i < K_CH; ++i) {
-            int j = min(j0 + k_row[i], N - 1);
-            rk[i] = *reinterpret_cast<const uint4*>(kbase + (int64_t)j * st + k_col[i]);
-        }
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i)
+            for (int i = 0; i < K_CH; ++i) rk[i] = *reinterpret_cast<const u32x4*>(kb + koff[i]);
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                int j = min(j0 + v_kg[i] * 8 + kk, N - 1);
-                rv[i][kk] = *reinterpret_cast<const uint32_t*>(vbase + (int64_t)j * st + v_d0[i]);
+                const bf16_t* vr = vb + (int64_t)kk * st;
+#pragma unroll
+                for (int i = 0; i < V_IT; ++i) rv[i][kk] = *reinterpret_cast<const uint32_t*>(vr + voff[i]);
             }
+        } else {   // last tile of the cache: rows past N-1 are clamped (they are masked anyway)
+            const int rmax = N - 1 - j0;
+#pragma unroll
+            for (int i = 0; i < K_CH; ++i) {
+                int r = min(k_r0 + i * (256 / KCPR), rmax);
+                rk[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)r * st + k_c);
+            }
+#pragma unroll
+            for (int i = 0; i < V_IT; ++i)
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    int r = min((v_kg0 + i * (256 / LPR)) * 8 + kk, rmax);
+                    rv[i][kk] = *reinterpret_cast<const uint32_t*>(vb + (int64_t)r * st + v_d);
+                }
+        }
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < K_CH; ++i) *reinterpret_cast<uint4*>(&Ks[buf][k_off[i]]) = rk[i];
+        for (int i = 0; i < K_CH; ++i) *reinterpret_cast<u32x4*>(&Ks[buf][k_lds[i]]) = rk[i];
 #pragma unroll
         for (int i = 0; i < V_IT; ++i) {
             // rv[i][kk] = (V[key kk][d0], V[key kk][d0+1]); regroup into 8 keys per d
-            uint4 lo, hi;
+            u32x4 lo, hi;
             lo.x = (rv[i][0] & 0xFFFFu) | (rv[i][1] << 16);
             lo.y = (rv[i][2] & 0xFFFFu) | (rv[i][3] << 16);
             lo.z = (rv[i][4] & 0xFFFFu) | (rv[i][5] << 16);
@@ -131,9 +145,15 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(
             hi.y = (rv[i][2] >> 16) | (rv[i][3] & 0xFFFF0000u);
             hi.z = (rv[i][4] >> 16) | (rv[i][5] & 0xFFFF0000u);
             hi.w = (rv[i][6] >> 16) | (rv[i][7] & 0xFFFF0000u);
-            int d0 = v_d0[i], kg = v_kg[i];
-            *reinterpret_cast<uint4*>(&Vt[buf][d0 * BN_KEYS + ((kg ^ (d0 & 7)) << 3)]) = lo;
-            *reinterpret_cast<uint4*>(&Vt[buf][(d0 + 1) * BN_KEYS + ((kg ^ ((d0 + 1) & 7)) << 3)]) = hi;
+            // rows with bit 3 of d set keep their two 8-byte halves swapped, so that the
+            // 16 lanes of one LDS read pass (d..d+15, same half) touch 16 distinct slots
+            const int d0 = v_d, kg = v_kg0 + i * (256 / LPR);
+            if (d0 & 8) {
+                lo = u32x4{lo.z, lo.w, lo.x, lo.y};
+                hi = u32x4{hi.z, hi.w, hi.x, hi.y};
+            }
+            *reinterpret_cast<u32x4*>(&Vt[buf][d0 * BN_KEYS + ((kg ^ (d0 & 7)) << 3)]) = lo;
+            *reinterpret_cast<u32x4*>(&Vt[buf][(d0 + 1) * BN_KEYS + ((kg ^ ((d0 + 1) & 7)) << 3)]) = hi;
         }
     };
 
@@ -169,37 +189,46 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(
                     s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
                 }
             }
-            // ---- scale, causal mask, online softmax (base 2) ----
+            // ---- causal mask (only in tiles that reach past the wave's first row),
+            //      online softmax in base 2 with the 1/sqrt(d_h) scale folded into the exponent ----
+            if (j0 + BN_KEYS - 1 > wave_min) {
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        int key = j0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+                        if (key > limit) s[kt][v] = -INFINITY;
+                    }
+            }
             float mx = -INFINITY;
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int key = j0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-                    float x = key <= limit ? s[kt][v] * scale_log2 : -INFINITY;
-                    s[kt][v] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kt][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
             const float m_new = fmaxf(m_run, mx);
             const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-            const float alpha = exp2f(m_run - m_use);
             float psum = 0.0f;
             bf16x8 pf[4];
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float p = exp2f(s[kt][v] - m_use);
+                    float p = __builtin_amdgcn_exp2f(fmaf(s[kt][v], scale_log2, -m_use));
                     psum += p;
                     pf[kt * 2 + (v >> 3)][v & 7] = (bf16_t)p;
                 }
-            l_run = l_run * alpha + psum;
+            // rescale only when some row's maximum moved
+            if (__any(m_new != m_run)) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc_o[dt][v] *= alpha;
+            }
+            l_run += psum;
             m_run = m_new;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc_o[dt][v] *= alpha;
             // ---- O^T += V^T P^T ----
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
@@ -208,8 +237,9 @@ __global__ __launch_bounds__(256) void sparse_attn_kernel(
 #pragma unroll
                 for (int ss = 0; ss < 4; ++ss) {
                     // slots 0..3 <- keys 16ss+4hf.., slots 4..7 <- keys 16ss+8+4hf..
-                    bf16x4 a0 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ss) ^ (d & 7)) << 3) + 4 * hf);
-                    bf16x4 a1 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ss + 1) ^ (d & 7)) << 3) + 4 * hf);
+                    const int hsel = 4 * (hf ^ ((d >> 3) & 1));
+                    bf16x4 a0 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ss) ^ (d & 7)) << 3) + hsel);
+                    bf16x4 a1 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ss + 1) ^ (d & 7)) << 3) + hsel);
                     bf16x8 vf;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {

@@ -12,6 +12,8 @@
 // double-buffered, XOR-swizzled LDS stage (global -> registers -> LDS, one
 // barrier per step).  The accumulators are written back through LDS so that
 // every global store is 16 or 32 contiguous bytes per lane along the row.
+#include <stdlib.h>
+
 #include "cc_internal.h"
 
 namespace {
@@ -35,11 +37,13 @@ struct BSingle {
 struct BDual {
     const bf16_t* B0;
     const bf16_t* B1;
-    int ldb;
+    int ldb, f;
     template <int BN>
     __device__ __forceinline__ const bf16_t* row(int bn, int r) const {
         constexpr int H = BN / 2;
-        return (r < H ? B0 + (int64_t)(bn * H + r) * ldb : B1 + (int64_t)(bn * H + r - H) * ldb);
+        int n = bn * H + (r < H ? r : r - H);
+        n = n < f ? n : f - 1;
+        return (r < H ? B0 : B1) + (int64_t)n * ldb;
     }
 };
 
@@ -177,8 +181,8 @@ __device__ __forceinline__ int xcd_remap(int bid, int nb) {
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
-    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, BSrc bsrc,
-    Epi epi) {
+    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int kstag,
+    BSrc bsrc, Epi epi) {
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -197,21 +201,21 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     const int bm = vb % tiles_m, bn = vb / tiles_m;   // neighbours share the weight tile
     const int m0 = bm * BM;
 
-    const uint4* ag[A_CH];
-    const uint4* bg[B_CH];
+    const u32x4* ag[A_CH];
+    const u32x4* bg[B_CH];
     int a_off[A_CH], b_off[B_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
         int c = tid + i * NT, r = c / CPR, kc = c % CPR;
         int m = m0 + r;
         m = m < M ? m : M - 1;
-        ag[i] = reinterpret_cast<const uint4*>(A + (int64_t)m * lda + kc * 8);
+        ag[i] = reinterpret_cast<const u32x4*>(A + (int64_t)m * lda + kc * 8);
         a_off[i] = r * BK + ((kc ^ (r & 7)) << 3);
     }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
         int c = tid + i * NT, r = c / CPR, kc = c % CPR;
-        bg[i] = reinterpret_cast<const uint4*>(bsrc.template row<BN>(bn, r) + kc * 8);
+        bg[i] = reinterpret_cast<const u32x4*>(bsrc.template row<BN>(bn, r) + kc * 8);
         b_off[i] = r * BK + ((kc ^ (r & 7)) << 3);
     }
 
@@ -223,57 +227,71 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    uint4 ra[A_CH], rb[B_CH];
+    // Row strides here are multiples of 4 KiB, so one K step of every row sits in
+    // the same memory channel.  Each workgroup therefore starts its K loop at a
+    // different column block (and wraps), which spreads concurrent workgroups
+    // over the channels.
+    const int KT = K / BK;
+    const int kt0 = (int)(((unsigned)vb * (unsigned)kstag) % (unsigned)KT);
+    auto kcol = [&](int kt) {
+        int k = kt + kt0;
+        return (k >= KT ? k - KT : k) * (BK / 8);
+    };
+    u32x4 ra[A_CH], rb[B_CH];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) ra[i] = ag[i][0];
+    for (int i = 0; i < A_CH; ++i) ra[i] = ag[i][kcol(0)];
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = bg[i][0];
+    for (int i = 0; i < B_CH; ++i) rb[i] = bg[i][kcol(0)];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(As + a_off[i]) = ra[i];
+    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(As + a_off[i]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(Bs + b_off[i]) = rb[i];
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(Bs + b_off[i]) = rb[i];
     __syncthreads();
 
-    const int KT = K / BK;
     const int frow = lane & 31, fk = lane >> 5;
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
         const bool more = kt + 1 < KT;
         if (more) {
 #pragma unroll
-            for (int i = 0; i < A_CH; ++i) ra[i] = ag[i][(kt + 1) * (BK / 8)];
+            for (int i = 0; i < A_CH; ++i) ra[i] = ag[i][kcol(kt + 1)];
 #pragma unroll
-            for (int i = 0; i < B_CH; ++i) rb[i] = bg[i][(kt + 1) * (BK / 8)];
+            for (int i = 0; i < B_CH; ++i) rb[i] = bg[i][kcol(kt + 1)];
         }
         const bf16_t* as = As + cur * BM * BK;
         const bf16_t* bs = Bs + cur * BN * BK;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[TM], bfr[TN];
+        bf16x8 af[2][TM], bfr[2][TN];
+        auto load_frags = [&](int ks, int fb) {
             const int kc = ks * 2 + fk;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 int r = wm0 + i * 32 + frow;
-                af[i] = *reinterpret_cast<const bf16x8*>(as + r * BK + ((kc ^ (r & 7)) << 3));
+                af[fb][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + ((kc ^ (r & 7)) << 3));
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 int r = wn0 + j * 32 + frow;
-                bfr[j] = *reinterpret_cast<const bf16x8*>(bs + r * BK + ((kc ^ (r & 7)) << 3));
+                bfr[fb][j] = *reinterpret_cast<const bf16x8*>(bs + r * BK + ((kc ^ (r & 7)) << 3));
             }
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) load_frags(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j],
+                                                                        acc[i][j], 0, 0, 0);
         }
         if (more) {
             bf16_t* an = As + (cur ^ 1) * BM * BK;
             bf16_t* bnx = Bs + (cur ^ 1) * BN * BK;
 #pragma unroll
-            for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(an + a_off[i]) = ra[i];
+            for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(an + a_off[i]) = ra[i];
 #pragma unroll
-            for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(bnx + b_off[i]) = rb[i];
+            for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(bnx + b_off[i]) = rb[i];
         }
         __syncthreads();
     }
@@ -309,7 +327,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
-void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, BSrc bsrc, Epi epi,
+void launch_gemm_cfg(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, BSrc bsrc, Epi epi,
                  hipStream_t s) {
     // N_tiles_cols: number of output columns covered by tiles of BN
     auto kern = gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, BSrc, Epi>;
@@ -321,8 +339,22 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, BSrc 
         attr_set = true;
     }
     int tiles_m = (M + BM - 1) / BM, tiles_n = (N_tiles_cols + BN - 1) / BN;
+    static const int kstag = getenv("CC_KSTAG") ? atoi(getenv("CC_KSTAG")) : 1;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, A, lda,
-                       M, K, tiles_m, tiles_n, bsrc, epi);
+                       M, K, tiles_m, tiles_n, kstag, bsrc, epi);
+}
+
+// Large row counts take 256x256 tiles (8 waves of 128x64: half the LDS traffic
+// per flop of the small tile); few rows take 128x128 tiles (4 waves of 64x64).
+template <class BSrc, class Epi>
+void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, BSrc bsrc, Epi epi,
+                 hipStream_t s) {
+    static const char* force = getenv("CC_GEMM_CFG");
+    const bool big = force ? force[0] == 'b' : M > 512;
+    if (big)
+        launch_gemm_cfg<256, 256, 2, 4>(A, lda, M, N_tiles_cols, K, bsrc, epi, s);
+    else
+        launch_gemm_cfg<128, 128, 2, 2>(A, lda, M, N_tiles_cols, K, bsrc, epi, s);
 }
 
 }  // namespace
@@ -335,7 +367,7 @@ void cc_launch_qkv(const bf16_t* xn, int M, const int32_t* idx, const bf16_t* w_
     BSingle b{w_qkv, m.d, N};
     EpiQKV e{idx, b_qkv, rope, m.H_q, m.H_kv, m.d_h, N, q_out,
              (bf16_t*)kv.K, (bf16_t*)kv.V, kv.stride_token, kv.stride_head};
-    launch_gemm<128, 128, 2, 2>(xn, m.d, M, N, m.d, b, e, s);
+    launch_gemm(xn, m.d, M, N, m.d, b, e, s);
 }
 
 void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hidden,
@@ -344,16 +376,16 @@ void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hi
     const int K = m.H_q * m.d_h;
     BSingle b{w_o, K, m.d};
     EpiOProj e{hidden, gather_idx, m.d, y};
-    launch_gemm<128, 128, 2, 2>(o, K, M, m.d, K, b, e, s);
+    launch_gemm(o, K, M, m.d, K, b, e, s);
 }
 
 void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16_t* w_up,
                        const cc_model_desc& m, bf16_t* act, hipStream_t s) {
     if (M <= 0) return;
-    BDual b{w_gate, w_up, m.d};
+    BDual b{w_gate, w_up, m.d, m.f};
     EpiGateUp e{m.f, act};
     // each 128-column tile holds 64 gate + 64 up columns: 2*f tile columns in total
-    launch_gemm<128, 128, 2, 2>(mn, m.d, M, 2 * m.f, m.d, b, e, s);
+    launch_gemm(mn, m.d, M, 2 * m.f, m.d, b, e, s);
 }
 
 void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float* y,
@@ -361,5 +393,5 @@ void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float*
     if (M <= 0) return;
     BSingle b{w_down, m.f, m.d};
     EpiDown e{y, m.d, out};
-    launch_gemm<128, 128, 2, 2>(act, m.f, M, m.d, m.f, b, e, s);
+    launch_gemm(act, m.f, M, m.d, m.f, b, e, s);
 }
