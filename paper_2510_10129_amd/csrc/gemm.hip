@@ -9,8 +9,8 @@
 //
 // Tiling: one workgroup of WAVES_M x WAVES_N waves computes a BM x BN tile with
 // v_mfma_f32_32x32x16_bf16; the K loop moves BK = 64 columns per step through a
-// double-buffered, XOR-swizzled LDS stage (global -> registers -> LDS, one
-// barrier per step).  The accumulators are written back through LDS so that
+// double-buffered, XOR-swizzled LDS stage filled by direct global->LDS loads
+// (no register staging), one barrier per step.  The accumulators are written back through LDS so that
 // every global store is 16 or 32 contiguous bytes per lane along the row.
 #include <stdlib.h>
 
@@ -20,7 +20,7 @@ namespace {
 
 constexpr int BK = 64;
 constexpr int CPR = BK / 8;   // 16-byte chunks per tile row
-constexpr int RG = 64;        // rows staged through LDS at a time in the epilogue
+constexpr int RG = 32;        // rows staged through LDS at a time in the epilogue
 
 struct BSingle {
     const bf16_t* B;
@@ -179,21 +179,32 @@ __device__ __forceinline__ int xcd_remap(int bid, int nb) {
     return x * q + (x < r ? x : r) + local;
 }
 
+// 16 bytes per lane straight from global memory into LDS (no VGPR staging, no
+// LDS store instruction).  The LDS destination is wave-uniform: lane L lands at
+// lds_base + 16*L.  Completion is tracked by vmcnt like any vector load.
+__device__ __forceinline__ void dma16(const bf16_t* gsrc, bf16_t* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds(
+        (const void __attribute__((address_space(1)))*)gsrc,
+        (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
-    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int kstag,
-    BSrc bsrc, Epi epi) {
-    constexpr int NT = WAVES_M * WAVES_N * 64;
+    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, BSrc bsrc,
+    Epi epi) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int NT = NW * 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;
+    constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;   // DMA instructions per wave and tile
     static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads");
     static_assert(BM % RG == 0 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
-    static_assert(RG * (BN + 4) * 4 <= 2 * (BM + BN) * BK * 2, "epilogue stage fits in the pipeline LDS");
+    static_assert(RG * (BN + 4) * 4 <= (BM + BN) * BK * 2, "epilogue stage fits in one pipeline stage");
 
-    extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [2][BM][BK]
-    bf16_t* Bs = As + 2 * BM * BK;                   // [2][BN][BK]
+    // Two pipeline stages as separate arrays, so that a DMA into one stage is
+    // known not to alias the fragment reads of the other.
+    __shared__ __align__(16) bf16_t st0[(BM + BN) * BK];
+    __shared__ __align__(16) bf16_t st1[(BM + BN) * BK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
@@ -201,23 +212,36 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     const int bm = vb % tiles_m, bn = vb / tiles_m;   // neighbours share the weight tile
     const int m0 = bm * BM;
 
-    const u32x4* ag[A_CH];
-    const u32x4* bg[B_CH];
-    int a_off[A_CH], b_off[B_CH];
+    // One DMA instruction moves 8 tile rows (8 x 128 B).  Lane L fills physical
+    // chunk slot L%8 of row L/8; the XOR swizzle (slot = chunk ^ ((row>>1)&7),
+    // conflict-free on the 64-bank LDS for 16-byte fragment reads) is applied by
+    // choosing which global chunk the lane fetches.
+    const bf16_t* ag[A_CH];
+    const bf16_t* bg[B_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
-        int c = tid + i * NT, r = c / CPR, kc = c % CPR;
+        int r = (i * NW + wave) * 8 + (lane >> 3);
+        int c = (lane & 7) ^ ((r >> 1) & 7);
         int m = m0 + r;
         m = m < M ? m : M - 1;
-        ag[i] = reinterpret_cast<const u32x4*>(A + (int64_t)m * lda + kc * 8);
-        a_off[i] = r * BK + ((kc ^ (r & 7)) << 3);
+        ag[i] = A + (int64_t)m * lda + c * 8;
     }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
-        int c = tid + i * NT, r = c / CPR, kc = c % CPR;
-        bg[i] = reinterpret_cast<const u32x4*>(bsrc.template row<BN>(bn, r) + kc * 8);
-        b_off[i] = r * BK + ((kc ^ (r & 7)) << 3);
+        int r = (i * NW + wave) * 8 + (lane >> 3);
+        int c = (lane & 7) ^ ((r >> 1) & 7);
+        bg[i] = bsrc.template row<BN>(bn, r) + c * 8;
     }
+    auto dma_tile = [&](bf16_t* stage, int kt) {
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) dma16(ag[i] + k0, stage + (i * NW + wave) * 8 * BK);
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) dma16(bg[i] + k0, stage + BM * BK + (i * NW + wave) * 8 * BK);
+        // keep the loads at the top of the iteration: the compiler would otherwise sink
+        // them below the MFMAs, next to the barrier that waits for them
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -227,52 +251,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // Row strides here are multiples of 4 KiB, so one K step of every row sits in
-    // the same memory channel.  Each workgroup therefore starts its K loop at a
-    // different column block (and wraps), which spreads concurrent workgroups
-    // over the channels.
-    const int KT = K / BK;
-    const int kt0 = (int)(((unsigned)vb * (unsigned)kstag) % (unsigned)KT);
-    auto kcol = [&](int kt) {
-        int k = kt + kt0;
-        return (k >= KT ? k - KT : k) * (BK / 8);
-    };
-    u32x4 ra[A_CH], rb[B_CH];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) ra[i] = ag[i][kcol(0)];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = bg[i][kcol(0)];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(As + a_off[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(Bs + b_off[i]) = rb[i];
-    __syncthreads();
-
     const int frow = lane & 31, fk = lane >> 5;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < A_CH; ++i) ra[i] = ag[i][kcol(kt + 1)];
-#pragma unroll
-            for (int i = 0; i < B_CH; ++i) rb[i] = bg[i][kcol(kt + 1)];
-        }
-        const bf16_t* as = As + cur * BM * BK;
-        const bf16_t* bs = Bs + cur * BN * BK;
+    const int fsw = (frow >> 1) & 7;      // rows of a fragment differ by multiples of 32
+    auto compute = [&](const bf16_t* stage) {
+        const bf16_t* as = stage;
+        const bf16_t* bs = stage + BM * BK;
         bf16x8 af[2][TM], bfr[2][TN];
         auto load_frags = [&](int ks, int fb) {
-            const int kc = ks * 2 + fk;
+            const int sl = ((ks * 2 + fk) ^ fsw) << 3;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int r = wm0 + i * 32 + frow;
-                af[fb][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + ((kc ^ (r & 7)) << 3));
-            }
+            for (int i = 0; i < TM; ++i)
+                af[fb][i] = *reinterpret_cast<const bf16x8*>(as + (wm0 + i * 32 + frow) * BK + sl);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int r = wn0 + j * 32 + frow;
-                bfr[fb][j] = *reinterpret_cast<const bf16x8*>(bs + r * BK + ((kc ^ (r & 7)) << 3));
-            }
+            for (int j = 0; j < TN; ++j)
+                bfr[fb][j] = *reinterpret_cast<const bf16x8*>(bs + (wn0 + j * 32 + frow) * BK + sl);
         };
         load_frags(0, 0);
 #pragma unroll
@@ -285,19 +277,30 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j],
                                                                         acc[i][j], 0, 0, 0);
         }
-        if (more) {
-            bf16_t* an = As + (cur ^ 1) * BM * BK;
-            bf16_t* bnx = Bs + (cur ^ 1) * BN * BK;
-#pragma unroll
-            for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(an + a_off[i]) = ra[i];
-#pragma unroll
-            for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(bnx + b_off[i]) = rb[i];
-        }
+    };
+
+    // K loop: while tile kt is multiplied out of one stage, the DMA engine fills
+    // the other with tile kt+1; the barrier at the end of the iteration waits for
+    // both (vmcnt for the DMA, every wave done reading).
+    const int KT = K / BK;
+    dma_tile(st0, 0);
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 2 <= KT; kt += 2) {
+        dma_tile(st1, kt + 1);
+        compute(st0);
+        __syncthreads();
+        if (kt + 2 < KT) dma_tile(st0, kt + 2);
+        compute(st1);
+        __syncthreads();
+    }
+    if (kt < KT) {
+        compute(st0);
         __syncthreads();
     }
 
     // ---- epilogue: accumulators -> LDS (fp32, RG rows at a time) -> fused store ----
-    float* stage = reinterpret_cast<float*>(smem);
+    float* stage = reinterpret_cast<float*>(st0);
     constexpr int LDS_LD = BN + 4;
     constexpr int TPR = BN / 8;           // threads per staged row
     constexpr int RPP = NT / TPR;         // rows per pass
@@ -331,17 +334,10 @@ void launch_gemm_cfg(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, B
                  hipStream_t s) {
     // N_tiles_cols: number of output columns covered by tiles of BN
     auto kern = gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, BSrc, Epi>;
-    constexpr int lds = 2 * (BM + BN) * BK * 2;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_set = true;
-    }
+    constexpr int lds = 0;
     int tiles_m = (M + BM - 1) / BM, tiles_n = (N_tiles_cols + BN - 1) / BN;
-    static const int kstag = getenv("CC_KSTAG") ? atoi(getenv("CC_KSTAG")) : 1;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, A, lda,
-                       M, K, tiles_m, tiles_n, kstag, bsrc, epi);
+                       M, K, tiles_m, tiles_n, bsrc, epi);
 }
 
 // Large row counts take 256x256 tiles (8 waves of 128x64: half the LDS traffic
