@@ -277,6 +277,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j],
                                                                         acc[i][j], 0, 0, 0);
         }
+        // issue order: the first k-step's fragments, then every MFMA followed by one
+        // fragment read of the next k-step, so LDS latency hides behind the matrix pipe
+        constexpr int NF = TM + TN, NM = TM * TN;
+        __builtin_amdgcn_sched_group_barrier(0x100, NF, 0);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks)
+#pragma unroll
+            for (int mm = 0; mm < NM; ++mm) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (ks + 1 < BK / 16 && mm < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
     };
 
     // K loop: while tile kt is multiplied out of one stage, the DMA engine fills
