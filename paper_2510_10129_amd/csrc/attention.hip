@@ -15,10 +15,13 @@
 // scalar, and the probabilities are already laid out as the B operand of
 // O^T = V^T P^T: no shuffle between the two contractions.
 //
-// K tiles sit in LDS as [key][d] (XOR-swizzled 16-byte chunks); V tiles are
-// transposed on the way in to [d][key] so that the PV contraction index (key)
-// is contiguous.  Both are double buffered: the next tile's global loads are
-// issued before the current tile's MFMAs.
+// K and V tiles (64 keys) go from the cache straight into LDS with 16-byte
+// global->LDS loads, row-major as they are stored, two stages each.  K
+// fragments are plain 16-byte LDS reads; the V^T fragments (contraction index =
+// key) come from the row-major V tile through the transposing LDS read
+// ds_read_b64_tr_b16, so V is never transposed in registers.  Both tiles are
+// XOR-swizzled (by choosing which global chunk a lane fetches) so that the
+// fragment reads spread over the 64 LDS banks.
 //
 // Causality with sorted idx: the key loop of a workgroup ends at the position
 // of its last row; the per-row mask only bites between the positions of the
@@ -31,20 +34,33 @@ namespace {
 
 constexpr int BN_KEYS = 64;
 
+__device__ __forceinline__ void dma16(const bf16_t* gsrc, bf16_t* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds(
+        (const void __attribute__((address_space(1)))*)gsrc,
+        (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
+}
+
+// Transposing LDS read.  Within each group of 16 lanes, lane i receives, as
+// element e, element (i % 4) of the 8-byte row addressed by lane (i / 4 + 4 e).
+__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)p);
+}
+
 template <int D_H>
 __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
     const bf16_t* __restrict__ q, int M, const int32_t* __restrict__ idx, int H_q, int H_kv,
     const bf16_t* __restrict__ Kc, const bf16_t* __restrict__ Vc, int64_t st, int64_t sh, int N,
     bf16_t* __restrict__ o, int n_row_tiles, float scale_log2) {
-    constexpr int KS = D_H / 16;        // k-steps of the QK^T contraction
-    constexpr int DT = D_H / 32;        // 32-row tiles of O^T
-    constexpr int KCPR = D_H / 8;       // 16-byte chunks per K row
-    constexpr int K_CH = BN_KEYS * KCPR / 256;
-    constexpr int LPR = D_H / 2;        // lanes per V row when each lane loads 2 elements
-    constexpr int V_IT = 8 * LPR / 256; // (key group, d pair) items per thread
+    constexpr int KS = D_H / 16;          // k-steps of the QK^T contraction
+    constexpr int DT = D_H / 32;          // 32-row tiles of O^T
+    constexpr int CPRW = D_H / 8;         // 16-byte chunks per cache row
+    constexpr int RPI = 64 / CPRW;        // rows moved by one global->LDS instruction
+    constexpr int NI = BN_KEYS / RPI / 4; // such instructions per wave, tile and tensor
 
-    __shared__ __align__(16) bf16_t Ks[2][BN_KEYS * D_H];
-    __shared__ __align__(16) bf16_t Vt[2][D_H * BN_KEYS];
+    __shared__ __align__(16) bf16_t Ks0[BN_KEYS * D_H];
+    __shared__ __align__(16) bf16_t Ks1[BN_KEYS * D_H];
+    __shared__ __align__(16) bf16_t Vs0[BN_KEYS * D_H];
+    __shared__ __align__(16) bf16_t Vs1[BN_KEYS * D_H];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = H_q / H_kv;
@@ -62,11 +78,10 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
     const int kmax = idx[last_row];                    // rows are sorted: the block's longest span
     const int n_tiles = kmax / BN_KEYS + 1;
 
-    // wave-wide largest limit: tiles beyond it are skipped by this wave
+    // wave-wide largest limit (tiles beyond it are skipped by this wave) and smallest
+    // limit of a valid row (tiles that end at or below it need no mask)
     int wave_limit = limit;
     for (int off = 32; off > 0; off >>= 1) wave_limit = max(wave_limit, __shfl_xor(wave_limit, off));
-
-    // wave-wide smallest limit of a valid row: tiles that end at or below it need no mask
     int wave_min = valid ? limit : 0x7fffffff;
     for (int off = 32; off > 0; off >>= 1) wave_min = min(wave_min, __shfl_xor(wave_min, off));
 
@@ -85,77 +100,52 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
         }
     }
 
-    // ---- global -> LDS staging: per-lane 32-bit offsets from a wave-uniform tile base ----
+    // ---- global -> LDS: instruction i of this wave moves rows (i*4+wave)*RPI .. +RPI-1;
+    //      lane L fills physical chunk L % CPRW of row L / CPRW and fetches the logical
+    //      chunk that the swizzle maps there ----
+    //   K rows: chunk c sits at slot c ^ kswz(row)           (16-byte fragment reads)
+    //   V rows: the 64-byte group dt sits at group dt ^ vswz(row)  (transposing 8-byte reads)
+    auto kswz = [](int r) { return D_H == 128 ? (r & 15) : ((r >> 1) & 7); };
+    auto vswz = [](int r) { return D_H == 128 ? (r & 3) : ((r >> 1) & 1); };
     const bf16_t* kbase = Kc + (int64_t)kvh * sh;
     const bf16_t* vbase = Vc + (int64_t)kvh * sh;
-    const int k_r0 = tid / KCPR, k_c = (tid % KCPR) * 8;      // chunk i: row k_r0 + i*(256/KCPR)
-    const int v_kg0 = tid / LPR, v_d = 2 * (tid % LPR);       // item i: key group v_kg0 + i*(256/LPR)
-    int koff[K_CH], k_lds[K_CH], voff[V_IT];
+    const int l_row = lane / CPRW, l_p = lane % CPRW;
+    int d_row[NI], k_col[NI], v_col[NI];
 #pragma unroll
-    for (int i = 0; i < K_CH; ++i) {
-        int r = k_r0 + i * (256 / KCPR);
-        koff[i] = r * (int)st + k_c;
-        k_lds[i] = r * D_H + (((k_c >> 3) ^ (r & 7)) << 3);
+    for (int i = 0; i < NI; ++i) {
+        const int r = (i * 4 + wave) * RPI + l_row;
+        d_row[i] = r;
+        k_col[i] = (l_p ^ kswz(r)) * 8;
+        v_col[i] = ((((l_p >> 2) ^ vswz(r)) << 2) | (l_p & 3)) * 8;
     }
-#pragma unroll
-    for (int i = 0; i < V_IT; ++i) voff[i] = (v_kg0 + i * (256 / LPR)) * 8 * (int)st + v_d;
-
-    u32x4 rk[K_CH];
-    uint32_t rv[V_IT][8];
-    auto load_tile = [&](int j0) {
+    auto dma_tile = [&](bf16_t* ks, bf16_t* vs, int j0) {
         const bf16_t* kb = kbase + (int64_t)j0 * st;
         const bf16_t* vb = vbase + (int64_t)j0 * st;
-        if (j0 + BN_KEYS <= N) {
+        const int rmax = N - 1 - j0;     // rows past the end of the cache are clamped (and masked)
 #pragma unroll
-            for (int i = 0; i < K_CH; ++i) rk[i] = *reinterpret_cast<const u32x4*>(kb + koff[i]);
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const bf16_t* vr = vb + (int64_t)kk * st;
-#pragma unroll
-                for (int i = 0; i < V_IT; ++i) rv[i][kk] = *reinterpret_cast<const uint32_t*>(vr + voff[i]);
-            }
-        } else {   // last tile of the cache: rows past N-1 are clamped (they are masked anyway)
-            const int rmax = N - 1 - j0;
-#pragma unroll
-            for (int i = 0; i < K_CH; ++i) {
-                int r = min(k_r0 + i * (256 / KCPR), rmax);
-                rk[i] = *reinterpret_cast<const u32x4*>(kb + (int64_t)r * st + k_c);
-            }
-#pragma unroll
-            for (int i = 0; i < V_IT; ++i)
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    int r = min((v_kg0 + i * (256 / LPR)) * 8 + kk, rmax);
-                    rv[i][kk] = *reinterpret_cast<const uint32_t*>(vb + (int64_t)r * st + v_d);
-                }
+        for (int i = 0; i < NI; ++i) {
+            const int r = min(d_row[i], rmax);
+            dma16(kb + (int64_t)r * st + k_col[i], ks + (i * 4 + wave) * RPI * D_H);
         }
-    };
-    auto store_tile = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < K_CH; ++i) *reinterpret_cast<u32x4*>(&Ks[buf][k_lds[i]]) = rk[i];
-#pragma unroll
-        for (int i = 0; i < V_IT; ++i) {
-            // rv[i][kk] = (V[key kk][d0], V[key kk][d0+1]); regroup into 8 keys per d
-            u32x4 lo, hi;
-            lo.x = (rv[i][0] & 0xFFFFu) | (rv[i][1] << 16);
-            lo.y = (rv[i][2] & 0xFFFFu) | (rv[i][3] << 16);
-            lo.z = (rv[i][4] & 0xFFFFu) | (rv[i][5] << 16);
-            lo.w = (rv[i][6] & 0xFFFFu) | (rv[i][7] << 16);
-            hi.x = (rv[i][0] >> 16) | (rv[i][1] & 0xFFFF0000u);
-            hi.y = (rv[i][2] >> 16) | (rv[i][3] & 0xFFFF0000u);
-            hi.z = (rv[i][4] >> 16) | (rv[i][5] & 0xFFFF0000u);
-            hi.w = (rv[i][6] >> 16) | (rv[i][7] & 0xFFFF0000u);
-            // rows with bit 3 of d set keep their two 8-byte halves swapped, so that the
-            // 16 lanes of one LDS read pass (d..d+15, same half) touch 16 distinct slots
-            const int d0 = v_d, kg = v_kg0 + i * (256 / LPR);
-            if (d0 & 8) {
-                lo = u32x4{lo.z, lo.w, lo.x, lo.y};
-                hi = u32x4{hi.z, hi.w, hi.x, hi.y};
-            }
-            *reinterpret_cast<u32x4*>(&Vt[buf][d0 * BN_KEYS + ((kg ^ (d0 & 7)) << 3)]) = lo;
-            *reinterpret_cast<u32x4*>(&Vt[buf][(d0 + 1) * BN_KEYS + ((kg ^ ((d0 + 1) & 7)) << 3)]) = hi;
+        for (int i = 0; i < NI; ++i) {
+            const int r = min(d_row[i], rmax);
+            dma16(vb + (int64_t)r * st + v_col[i], vs + (i * 4 + wave) * RPI * D_H);
         }
+        __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the tile's math
     };
+
+    // ---- fragment addresses ----
+    // K: row kt*32 + qr, logical chunk 2 ks + hf
+    const int k_frag_row = qr * D_H;
+    const int k_sw = kswz(qr);
+    // V^T through the transposing read: lane s of a 16-lane group addresses key
+    // (4 hf + s/4) and the 4 d's starting at 16*(group%2) + 4*(s%4); the lane then
+    // holds 4 consecutive keys of column d = 32 dt + lane%32.
+    const int s16 = lane & 15, dsub = (lane >> 4) & 1;
+    const int v_key = 4 * hf + (s16 >> 2);
+    const int v_sw = vswz(v_key);
+    const int v_lane = v_key * D_H + (2 * dsub + ((s16 & 3) >> 1)) * 8 + (s16 & 1) * 4;
 
     f32x16 acc_o[DT];
 #pragma unroll
@@ -164,94 +154,93 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
         for (int v = 0; v < 16; ++v) acc_o[dt][v] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int t = 0; t < n_tiles; ++t) {
-        const int cur = t & 1;
-        const int j0 = t * BN_KEYS;
-        const bool more = t + 1 < n_tiles;
-        if (more) load_tile(j0 + BN_KEYS);
-
-        if (j0 <= wave_limit) {
-            // ---- S^T tile: 64 keys x 32 query rows ----
-            f32x16 s[2];
+    auto tile_math = [&](const bf16_t* ks_, const bf16_t* vs_, int j0) {
+        // ---- S^T tile: 64 keys x 32 query rows ----
+        f32x16 s[2];
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
+        for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) s[kt][v] = 0.0f;
-                const int r = kt * 32 + qr;
+            for (int v = 0; v < 16; ++v) s[kt][v] = 0.0f;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const int kc = ks * 2 + hf;
-                    bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Ks[cur][r * D_H + ((kc ^ (r & 7)) << 3)]);
-                    s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
-                }
+            for (int ks = 0; ks < KS; ++ks) {
+                const int kc = (ks * 2 + hf) ^ k_sw;
+                bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks_ + kt * 32 * D_H + k_frag_row + (kc << 3));
+                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
             }
-            // ---- causal mask (only in tiles that reach past the wave's first row),
-            //      online softmax in base 2 with the 1/sqrt(d_h) scale folded into the exponent ----
-            if (j0 + BN_KEYS - 1 > wave_min) {
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int key = j0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-                        if (key > limit) s[kt][v] = -INFINITY;
-                    }
-            }
-            float mx = -INFINITY;
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kt][v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-            float psum = 0.0f;
-            bf16x8 pf[4];
+        }
+        // ---- causal mask (only in tiles that reach past the wave's first row),
+        //      online softmax in base 2 with the 1/sqrt(d_h) scale folded into the exponent ----
+        if (j0 + BN_KEYS - 1 > wave_min) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float p = __builtin_amdgcn_exp2f(fmaf(s[kt][v], scale_log2, -m_use));
-                    psum += p;
-                    pf[kt * 2 + (v >> 3)][v & 7] = (bf16_t)p;
+                    int key = j0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+                    if (key > limit) s[kt][v] = -INFINITY;
                 }
-            // rescale only when some row's maximum moved
-            if (__any(m_new != m_run)) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-                l_run *= alpha;
+        }
+        float mx = -INFINITY;
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc_o[dt][v] *= alpha;
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kt][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+        float psum = 0.0f;
+        bf16x8 pf[4];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float p = __builtin_amdgcn_exp2f(fmaf(s[kt][v], scale_log2, -m_use));
+                psum += p;
+                pf[kt * 2 + (v >> 3)][v & 7] = (bf16_t)p;
             }
-            l_run += psum;
-            m_run = m_new;
-            // ---- O^T += V^T P^T ----
+        // rescale only when some row's maximum moved
+        if (__any(m_new != m_run)) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+            l_run *= alpha;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                const int d = dt * 32 + qr;
-                const bf16_t* vrow = &Vt[cur][d * BN_KEYS];
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int ss = 0; ss < 4; ++ss) {
-                    // slots 0..3 <- keys 16ss+4hf.., slots 4..7 <- keys 16ss+8+4hf..
-                    const int hsel = 4 * (hf ^ ((d >> 3) & 1));
-                    bf16x4 a0 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ss) ^ (d & 7)) << 3) + hsel);
-                    bf16x4 a1 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ss + 1) ^ (d & 7)) << 3) + hsel);
-                    bf16x8 vf;
+                for (int v = 0; v < 16; ++v) acc_o[dt][v] *= alpha;
+        }
+        l_run += psum;
+        m_run = m_new;
+        // ---- O^T += V^T P^T: slots 0..3 <- keys 16ss+4hf.., slots 4..7 <- keys 16ss+8+4hf.. ----
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        vf[u] = a0[u];
-                        vf[4 + u] = a1[u];
-                    }
-                    acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ss], acc_o[dt], 0, 0, 0);
+        for (int dt = 0; dt < DT; ++dt) {
+            const bf16_t* vcol = vs_ + v_lane + ((dt ^ v_sw) << 5);
+#pragma unroll
+            for (int ss = 0; ss < 4; ++ss) {
+                bf16x4 a0 = lds_read_tr(vcol + (16 * ss) * D_H);
+                bf16x4 a1 = lds_read_tr(vcol + (16 * ss + 8) * D_H);
+                bf16x8 vf;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    vf[u] = a0[u];
+                    vf[4 + u] = a1[u];
                 }
+                acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ss], acc_o[dt], 0, 0, 0);
             }
         }
-        if (more) store_tile(cur ^ 1);
+    };
+
+    // ---- key loop: the next tile streams into the idle stage while this one is used;
+    //      the barrier waits for the loads (vmcnt) and for every wave to leave the stage ----
+    dma_tile(Ks0, Vs0, 0);
+    __syncthreads();
+    for (int t = 0; t < n_tiles; t += 2) {
+        const int j0 = t * BN_KEYS;
+        if (t + 1 < n_tiles) dma_tile(Ks1, Vs1, j0 + BN_KEYS);
+        if (j0 <= wave_limit) tile_math(Ks0, Vs0, j0);
         __syncthreads();
+        if (t + 1 < n_tiles) {
+            if (t + 2 < n_tiles) dma_tile(Ks0, Vs0, j0 + 2 * BN_KEYS);
+            if (j0 + BN_KEYS <= wave_limit) tile_math(Ks1, Vs1, j0 + BN_KEYS);
+            __syncthreads();
+        }
     }
 
     // ---- normalise and write: lane holds 4 consecutive d per (dt, v/4) ----
