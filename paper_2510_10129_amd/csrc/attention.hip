@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
     __shared__ __align__(16) bf16_t Vs0[BN_KEYS * D_H];
     __shared__ __align__(16) bf16_t Vs1[BN_KEYS * D_H];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform (scalar) on purpose
     const int g = H_q / H_kv;
     const int tw = 32 / g;              // tokens per wave
     const int BT = 4 * tw;              // tokens per workgroup
@@ -110,27 +111,32 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
     const bf16_t* kbase = Kc + (int64_t)kvh * sh;
     const bf16_t* vbase = Vc + (int64_t)kvh * sh;
     const int l_row = lane / CPRW, l_p = lane % CPRW;
-    int d_row[NI], k_col[NI], v_col[NI];
+    int d_row[NI], k_col[NI], v_col[NI], koff[NI], voff[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int r = (i * 4 + wave) * RPI + l_row;
         d_row[i] = r;
         k_col[i] = (l_p ^ kswz(r)) * 8;
         v_col[i] = ((((l_p >> 2) ^ vswz(r)) << 2) | (l_p & 3)) * 8;
+        koff[i] = r * (int)st + k_col[i];     // 32-bit lane offsets from a wave-uniform tile base
+        voff[i] = r * (int)st + v_col[i];
     }
     auto dma_tile = [&](bf16_t* ks, bf16_t* vs, int j0) {
         const bf16_t* kb = kbase + (int64_t)j0 * st;
         const bf16_t* vb = vbase + (int64_t)j0 * st;
-        const int rmax = N - 1 - j0;     // rows past the end of the cache are clamped (and masked)
+        if (j0 + BN_KEYS <= N) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int r = min(d_row[i], rmax);
-            dma16(kb + (int64_t)r * st + k_col[i], ks + (i * 4 + wave) * RPI * D_H);
-        }
+            for (int i = 0; i < NI; ++i) dma16(kb + koff[i], ks + (i * 4 + wave) * RPI * D_H);
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int r = min(d_row[i], rmax);
-            dma16(vb + (int64_t)r * st + v_col[i], vs + (i * 4 + wave) * RPI * D_H);
+            for (int i = 0; i < NI; ++i) dma16(vb + voff[i], vs + (i * 4 + wave) * RPI * D_H);
+        } else {   // last tile of the cache: rows past N-1 are clamped (they are masked anyway)
+            const int rmax = N - 1 - j0;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int r = min(d_row[i], rmax);
+                dma16(kb + (int64_t)r * st + k_col[i], ks + (i * 4 + wave) * RPI * D_H);
+                dma16(vb + (int64_t)r * st + v_col[i], vs + (i * 4 + wave) * RPI * D_H);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the tile's math
     };
@@ -158,12 +164,15 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
         // ---- S^T tile: 64 keys x 32 query rows ----
         f32x16 s[2];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[kt][v] = 0.0f;
+        // the two 32-key halves are independent accumulation chains: alternate them
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int kc = (ks * 2 + hf) ^ k_sw;
+        for (int ks = 0; ks < KS; ++ks) {
+            const int kc = (ks * 2 + hf) ^ k_sw;
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
                 bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks_ + kt * 32 * D_H + k_frag_row + (kc << 3));
                 s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
             }
@@ -185,8 +194,22 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kt][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+        // The reference point m_run of the exponent is only moved when a row's maximum
+        // grew by more than 2^8: until then probabilities up to 256 are accumulated
+        // (harmless in fp32 / bf16, and the final division by the row sum cancels it),
+        // which keeps the 64-element rescale of O out of most tiles.
+        const bool grow = mx > m_run + 8.0f;
+        if (__any(grow)) {
+            const float m_new = grow ? mx : m_run;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.0f : m_new));
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc_o[dt][v] *= alpha;
+            m_run = m_new;
+        }
+        const float m_use = m_run == -INFINITY ? 0.0f : m_run;
         float psum = 0.0f;
         bf16x8 pf[4];
 #pragma unroll
@@ -197,23 +220,13 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
                 psum += p;
                 pf[kt * 2 + (v >> 3)][v & 7] = (bf16_t)p;
             }
-        // rescale only when some row's maximum moved
-        if (__any(m_new != m_run)) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-            l_run *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc_o[dt][v] *= alpha;
-        }
         l_run += psum;
-        m_run = m_new;
         // ---- O^T += V^T P^T: slots 0..3 <- keys 16ss+4hf.., slots 4..7 <- keys 16ss+8+4hf.. ----
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const bf16_t* vcol = vs_ + v_lane + ((dt ^ v_sw) << 5);
+        for (int ss = 0; ss < 4; ++ss) {
 #pragma unroll
-            for (int ss = 0; ss < 4; ++ss) {
+            for (int dt = 0; dt < DT; ++dt) {      // DT independent accumulation chains
+                const bf16_t* vcol = vs_ + v_lane + ((dt ^ v_sw) << 5);
                 bf16x4 a0 = lds_read_tr(vcol + (16 * ss) * D_H);
                 bf16x4 a1 = lds_read_tr(vcol + (16 * ss + 8) * D_H);
                 bf16x8 vf;
