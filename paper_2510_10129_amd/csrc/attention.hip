@@ -78,6 +78,14 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
     const int last_row = min(M - 1, rt * BT + BT - 1);
     const int kmax = idx[last_row];                    // rows are sorted: the block's longest span
     const int n_tiles = kmax / BN_KEYS + 1;
+    // Workgroups with the longest key loops decide when the kernel ends: give their
+    // waves issue priority over the short ones they share a SIMD with.
+    {
+        const int q4 = (4 * n_tiles) / ((N + BN_KEYS - 1) / BN_KEYS + 1);
+        if (q4 >= 3) __builtin_amdgcn_s_setprio(3);
+        else if (q4 == 2) __builtin_amdgcn_s_setprio(2);
+        else if (q4 == 1) __builtin_amdgcn_s_setprio(1);
+    }
 
     // wave-wide largest limit (tiles beyond it are skipped by this wave) and smallest
     // limit of a valid row (tiles that end at or below it need no mask)

@@ -351,14 +351,30 @@ void launch_gemm_cfg(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, B
                        M, K, tiles_m, tiles_n, bsrc, epi);
 }
 
-// Large row counts take 256x256 tiles (8 waves of 128x64: half the LDS traffic
-// per flop of the small tile); few rows take 128x128 tiles (4 waves of 64x64).
+// Two tile shapes: 256x256 (8 waves of 128x64, least LDS and L1 traffic per
+// flop, one workgroup per CU) and 128x128 (4 waves of 64x64, two per CU, about
+// 0.88 of the large tile's rate).  A grid runs as a whole number of "rounds" of
+// workgroups, so the shape is chosen per launch to minimise rounds x tile cost.
 template <class BSrc, class Epi>
 void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, BSrc bsrc, Epi epi,
                  hipStream_t s) {
+    static const int n_cu = [] {
+        int dev = 0, n = 256;
+        if (hipGetDevice(&dev) == hipSuccess)
+            (void)hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        return n > 0 ? n : 256;
+    }();
     static const char* force = getenv("CC_GEMM_CFG");
-    const bool big = force ? force[0] == 'b' : M > 512;
-    if (big)
+    auto cost = [&](int bm, int bn, int per_cu, double eff) {
+        const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn);
+        const long slots = (long)n_cu * per_cu;
+        const long rounds = (tiles + slots - 1) / slots;
+        return (double)rounds * per_cu * bm * bn / eff;
+    };
+    const double cb = cost(256, 256, 1, 1.00), cs = cost(128, 128, 2, 0.88);
+    char pick = cb <= cs ? 'b' : 's';
+    if (force) pick = force[0];
+    if (pick == 'b')
         launch_gemm_cfg<256, 256, 2, 4>(A, lda, M, N_tiles_cols, K, bsrc, epi, s);
     else
         launch_gemm_cfg<128, 128, 2, 2>(A, lda, M, N_tiles_cols, K, bsrc, epi, s);
