@@ -46,7 +46,7 @@ typedef struct cc_ctx cc_ctx;
 
 /* Shape of the primary model's decoder layer and the capacity of the context. */
 typedef struct cc_model_desc {
-    int32_t d;         /* hidden width; multiple of 64 */
+    int32_t d;         /* hidden width; multiple of 64, at most 16384 */
     int32_t H_q;       /* query heads */
     int32_t H_kv;      /* key/value heads; divides H_q, H_q / H_kv <= 32 */
     int32_t d_h;       /* head dim: 64 or 128 */

@@ -25,7 +25,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 cc_status check_model(const cc_model_desc& m, std::string* why) {
     auto bad = [&](const char* s) { *why = s; return CC_ERR_SHAPE; };
-    if (m.d < 64 || m.d % 64) return bad("d must be a positive multiple of 64");
+    if (m.d < 64 || m.d % 64 || m.d > 16384) return bad("d must be a multiple of 64 in [64, 16384]");
     if (m.f < 64 || m.f % 64) return bad("f must be a positive multiple of 64");
     if (m.d_h != 64 && m.d_h != 128) return bad("d_h must be 64 or 128");
     if (m.H_q < 1 || m.H_kv < 1 || m.H_q % m.H_kv) return bad("H_kv must divide H_q");

@@ -2,86 +2,110 @@
 // RMSNorm of the fp32 residual stream, and the rotary table.
 #include "cc_internal.h"
 
-__device__ __forceinline__ float block_sum_256(float v, float* red) {
+__device__ __forceinline__ float wave_sum(float v) {
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) red[wave] = v;
-    __syncthreads();
-    float t = red[0] + red[1] + red[2] + red[3];
-    __syncthreads();
-    return t;
+    return v;
 }
 
-// One workgroup per recomputed token: reads row gather_idx[i] of `hidden`
-// (16 bytes per lane, whole 128-byte lines per 8 lanes), reduces the mean
-// square in fp32, and writes the normalised bf16 row.  The second sweep over
-// the row is served from cache.
+// One wave per recomputed token, the whole row held in registers between the
+// sum of squares and the scaled write (one pass over HBM): lane L owns the
+// 16-byte chunks L, L+64, ... of row gather_idx[i], so every load and store of a
+// wave covers 1 KiB of contiguous row.  NCH = chunks per lane (d <= 512*NCH).
+template <int NCH>
 __global__ __launch_bounds__(256) void gather_rmsnorm_kernel(
-    const bf16_t* __restrict__ hidden, const int32_t* __restrict__ gather_idx, int d,
+    const bf16_t* __restrict__ hidden, const int32_t* __restrict__ gather_idx, int M, int d,
     const bf16_t* __restrict__ w, float eps, bf16_t* __restrict__ xn) {
-    __shared__ float red[4];
-    const int i = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= M) return;
     const int64_t src = gather_idx ? (int64_t)gather_idx[i] : (int64_t)i;
     const bf16x8* row = reinterpret_cast<const bf16x8*>(hidden + src * d);
     const bf16x8* wv = reinterpret_cast<const bf16x8*>(w);
     bf16x8* dst = reinterpret_cast<bf16x8*>(xn + (int64_t)i * d);
     const int nchunk = d >> 3;
+    bf16x8 v[NCH];
     float ss = 0.0f;
-    for (int c = threadIdx.x; c < nchunk; c += 256) {
-        bf16x8 v = row[c];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            float f = (float)v[u];
-            ss += f * f;
+    for (int c = 0; c < NCH; ++c)
+        if (lane + 64 * c < nchunk) v[c] = __builtin_nontemporal_load(row + lane + 64 * c);
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+        if (lane + 64 * c < nchunk) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                float f = (float)v[c][u];
+                ss += f * f;
+            }
         }
-    }
-    float tot = block_sum_256(ss, red);
-    float r = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int c = threadIdx.x; c < nchunk; c += 256) {
-        bf16x8 v = row[c], g = wv[c], o;
+    const float r = 1.0f / sqrtf(wave_sum(ss) / (float)d + eps);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) o[u] = (bf16_t)((float)v[u] * r * (float)g[u]);
-        dst[c] = o;
-    }
+    for (int c = 0; c < NCH; ++c)
+        if (lane + 64 * c < nchunk) {
+            bf16x8 g = wv[lane + 64 * c], o;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) o[u] = (bf16_t)((float)v[c][u] * r * (float)g[u]);
+            dst[lane + 64 * c] = o;
+        }
 }
 
 void cc_launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* gather_idx, int M, int d,
                               const bf16_t* w, float eps, bf16_t* xn, hipStream_t s) {
     if (M <= 0) return;
-    hipLaunchKernelGGL(gather_rmsnorm_kernel, dim3(M), dim3(256), 0, s, hidden, gather_idx, d, w,
-                       eps, xn);
+    dim3 grid((M + 3) / 4), block(256);
+    if (d <= 1024)
+        hipLaunchKernelGGL(gather_rmsnorm_kernel<2>, grid, block, 0, s, hidden, gather_idx, M, d, w, eps, xn);
+    else if (d <= 4096)
+        hipLaunchKernelGGL(gather_rmsnorm_kernel<8>, grid, block, 0, s, hidden, gather_idx, M, d, w, eps, xn);
+    else if (d <= 8192)
+        hipLaunchKernelGGL(gather_rmsnorm_kernel<16>, grid, block, 0, s, hidden, gather_idx, M, d, w, eps, xn);
+    else
+        hipLaunchKernelGGL(gather_rmsnorm_kernel<32>, grid, block, 0, s, hidden, gather_idx, M, d, w, eps, xn);
 }
 
-// RMSNorm of the fp32 residual rows y [M, d] -> bf16.
-__global__ __launch_bounds__(256) void rmsnorm_f32_kernel(const float* __restrict__ y, int d,
+// RMSNorm of the fp32 residual rows y [M, d] -> bf16, same scheme (lane owns
+// 16-byte chunks of 4 floats; NCH chunks per lane, d <= 256*NCH).
+template <int NCH>
+__global__ __launch_bounds__(256) void rmsnorm_f32_kernel(const float* __restrict__ y, int M, int d,
                                                           const bf16_t* __restrict__ w, float eps,
                                                           bf16_t* __restrict__ out) {
-    __shared__ float red[4];
-    const int i = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= M) return;
     const f32x4* row = reinterpret_cast<const f32x4*>(y + (int64_t)i * d);
     const bf16x4* wv = reinterpret_cast<const bf16x4*>(w);
     bf16x4* dst = reinterpret_cast<bf16x4*>(out + (int64_t)i * d);
     const int nchunk = d >> 2;
+    f32x4 v[NCH];
     float ss = 0.0f;
-    for (int c = threadIdx.x; c < nchunk; c += 256) {
-        f32x4 v = row[c];
-        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-    }
-    float tot = block_sum_256(ss, red);
-    float r = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int c = threadIdx.x; c < nchunk; c += 256) {
-        f32x4 v = row[c];
-        bf16x4 g = wv[c], o;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) o[u] = (bf16_t)(v[u] * r * (float)g[u]);
-        dst[c] = o;
-    }
+    for (int c = 0; c < NCH; ++c)
+        if (lane + 64 * c < nchunk) v[c] = row[lane + 64 * c];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+        if (lane + 64 * c < nchunk) ss += v[c][0] * v[c][0] + v[c][1] * v[c][1] + v[c][2] * v[c][2] + v[c][3] * v[c][3];
+    const float r = 1.0f / sqrtf(wave_sum(ss) / (float)d + eps);
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+        if (lane + 64 * c < nchunk) {
+            bf16x4 g = wv[lane + 64 * c], o;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) o[u] = (bf16_t)(v[c][u] * r * (float)g[u]);
+            dst[lane + 64 * c] = o;
+        }
 }
 
 void cc_launch_rmsnorm_f32(const float* y, int M, int d, const bf16_t* w, float eps, bf16_t* out,
                            hipStream_t s) {
     if (M <= 0) return;
-    hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3(M), dim3(256), 0, s, y, d, w, eps, out);
+    dim3 grid((M + 3) / 4), block(256);
+    if (d <= 1024)
+        hipLaunchKernelGGL(rmsnorm_f32_kernel<4>, grid, block, 0, s, y, M, d, w, eps, out);
+    else if (d <= 4096)
+        hipLaunchKernelGGL(rmsnorm_f32_kernel<16>, grid, block, 0, s, y, M, d, w, eps, out);
+    else if (d <= 8192)
+        hipLaunchKernelGGL(rmsnorm_f32_kernel<32>, grid, block, 0, s, y, M, d, w, eps, out);
+    else
+        hipLaunchKernelGGL(rmsnorm_f32_kernel<64>, grid, block, 0, s, y, M, d, w, eps, out);
 }
 
 // Rotary table: entry (p, j) = (cos, sin) of p * base^(-2j/d_h), evaluated in

@@ -8,8 +8,8 @@
 // over its query rows (Section 4.2).  One lane owns one column and adds the
 // rows in ascending order with a single fp32 accumulator, so the result is
 // the same bit pattern on every run and on any host that adds in that order.
-// Loads of 16 rows are issued together; a wave reads 256 contiguous bytes per
-// row.
+// Loads of 32 rows are issued together (the kernel is bound by load latency,
+// not by adds); a wave reads 256 contiguous bytes per row.
 // ----------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void colsum_kernel(const float* __restrict__ attn, int Q_a, int T,
                                                     int64_t ld, float* __restrict__ score) {
@@ -18,12 +18,12 @@ __global__ __launch_bounds__(64) void colsum_kernel(const float* __restrict__ at
     const float* p = attn + t;
     float acc = 0.0f;
     int q = 0;
-    for (; q + 16 <= Q_a; q += 16) {
-        float v[16];
+    for (; q + 32 <= Q_a; q += 32) {
+        float v[32];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = __builtin_nontemporal_load(p + (int64_t)(q + u) * ld);
+        for (int u = 0; u < 32; ++u) v[u] = __builtin_nontemporal_load(p + (int64_t)(q + u) * ld);
 #pragma unroll
-        for (int u = 0; u < 16; ++u) acc = acc + v[u];
+        for (int u = 0; u < 32; ++u) acc = acc + v[u];
     }
     for (; q < Q_a; ++q) acc = acc + p[(int64_t)q * ld];
     score[t] = acc;
