@@ -8,19 +8,21 @@
 //   DOWN    + residual stream -> bf16 layer output
 //
 // Tiling: one workgroup of WAVES_M x WAVES_N waves computes a BM x BN tile with
-// v_mfma_f32_32x32x16_bf16; the K loop moves BK = 64 columns per step through a
-// double-buffered, XOR-swizzled LDS stage filled by direct global->LDS loads
-// (no register staging), one barrier per step.  The accumulators are written back through LDS so that
-// every global store is 16 or 32 contiguous bytes per lane along the row.
+// v_mfma_f32_32x32x16_bf16.  Operands go from global memory straight into LDS
+// (16-byte global->LDS loads, no register staging), XOR-swizzled so that the
+// 16-byte fragment reads are conflict-free on the 64-bank LDS.  Two K loops:
+//   ring   (K % 128 == 0) slices of 32 columns in a ring of four LDS slots; a
+//          slice is requested three slices (96 columns of MFMA work) before it is
+//          read, which hides the L2/fabric latency that a two-stage pipeline
+//          exposes; one barrier per slice, waits by explicit vmcnt.
+//   staged (any K % 64 == 0) two stages of 64 columns, one barrier per stage.
+// The accumulators are written back through LDS so that every global store is
+// 16 or 32 contiguous bytes per lane along the row.
 #include <stdlib.h>
 
 #include "cc_internal.h"
 
 namespace {
-
-constexpr int BK = 64;
-constexpr int CPR = BK / 8;   // 16-byte chunks per tile row
-constexpr int RG = 32;        // rows staged through LDS at a time in the epilogue
 
 struct BSingle {
     const bf16_t* B;
@@ -30,6 +32,19 @@ struct BSingle {
         int n = bn * BN + r;
         n = n < N ? n : N - 1;
         return B + (int64_t)n * ldb;
+    }
+    // ring loop: tile rows [half*BN/2, (half+1)*BN/2) start at base() and there are
+    // rows_left() valid rows from there (rows past the end are clamped by the caller)
+    template <int BN>
+    __device__ __forceinline__ const bf16_t* base(int bn, int half) const {
+        int n0 = bn * BN + half * (BN / 2);
+        n0 = n0 < N ? n0 : N - 1;
+        return B + (int64_t)n0 * ldb;
+    }
+    template <int BN>
+    __device__ __forceinline__ int rows_left(int bn, int half) const {
+        const int l = N - bn * BN - half * (BN / 2);
+        return l < 1 ? 1 : l;
     }
 };
 
@@ -44,6 +59,17 @@ struct BDual {
         int n = bn * H + (r < H ? r : r - H);
         n = n < f ? n : f - 1;
         return (r < H ? B0 : B1) + (int64_t)n * ldb;
+    }
+    template <int BN>
+    __device__ __forceinline__ const bf16_t* base(int bn, int half) const {
+        int n0 = bn * (BN / 2);
+        n0 = n0 < f ? n0 : f - 1;
+        return (half ? B1 : B0) + (int64_t)n0 * ldb;
+    }
+    template <int BN>
+    __device__ __forceinline__ int rows_left(int bn, int half) const {
+        const int l = f - bn * (BN / 2);
+        return l < 1 ? 1 : l;
     }
 };
 
@@ -171,12 +197,21 @@ struct EpiDown {
 };
 
 // Consecutive workgroup ids go round-robin to the 8 XCDs (each with its own
-// L2); give every XCD one contiguous range of tiles so that workgroups sharing
-// a weight tile also share an L2.
-__device__ __forceinline__ int xcd_remap(int bid, int nb) {
+// L2).  Every XCD gets one contiguous range of the tile sequence, and the
+// sequence walks bands of GM row-tiles column by column, so the workgroups that
+// run together on an XCD form a GM x (32/GM) block of tiles: they share GM
+// tiles of A and 32/GM tiles of B through that L2.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int GM, int* bm,
+                                              int* bn) {
+    const int nb = tiles_m * tiles_n;
     const int q = nb >> 3, r = nb & 7;
     const int x = bid & 7, local = bid >> 3;
-    return x * q + (x < r ? x : r) + local;
+    const int vb = x * q + (x < r ? x : r) + local;
+    const int band = GM * tiles_n;
+    const int b = vb / band, rb = vb - b * band;
+    const int gm = min(GM, tiles_m - b * GM);
+    *bm = b * GM + rb % gm;
+    *bn = rb / gm;
 }
 
 // 16 bytes per lane straight from global memory into LDS (no VGPR staging, no
@@ -188,9 +223,64 @@ __device__ __forceinline__ void dma16(const bf16_t* gsrc, bf16_t* lds_wave_base)
         (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
 }
 
+// s_waitcnt: at most N vector-memory operations outstanding, no LDS operation.
+template <int N>
+__device__ __forceinline__ void wait_vm_lds0() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4));
+}
+
+// Accumulators -> LDS (fp32, RG rows at a time) -> fused store.  `stage` must
+// hold RG * (BN + 4) floats and no wave may still be reading operands from it.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int RG, class Epi>
+__device__ __forceinline__ void store_tile(f32x16 (&acc)[BM / WAVES_M / 32][BN / WAVES_N / 32],
+                                           float* stage, int m0, int bn, int M, const Epi& epi) {
+    constexpr int NT = WAVES_M * WAVES_N * 64;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int LDS_LD = BN + 4;
+    constexpr int TPR = BN / 8;           // threads per staged row
+    constexpr int RPP = NT / TPR;         // rows per pass
+    static_assert(RG == 32 || RG == 16, "row group");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+    const int frow = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int rg = 0; rg < BM / RG; ++rg) {
+        if (rg) __syncthreads();
+        // register v of a 32x32 accumulator tile holds tile row 8*(v>>2) + 4*fk + (v&3):
+        // the rows of this group are those of one accumulator tile (or of its half `sub`)
+        constexpr int VPG = 16 * RG / 32;                 // accumulator registers per row group
+        const int sub = (rg * RG % 32) / RG;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int tr = wm0 + i * 32;                  // first row of this accumulator tile
+            if (tr / 32 == rg * RG / 32) {                // wave-uniform
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int vv = 0; vv < VPG; ++vv) {
+                        const int v = sub * VPG + vv;
+                        const int r = 8 * (v >> 2) + 4 * fk + (v & 3) - sub * RG;
+                        stage[r * LDS_LD + wn0 + j * 32 + frow] = acc[i][j][v];
+                    }
+            }
+        }
+        __syncthreads();
+        const int cc = (tid % TPR) * 8;
+        for (int r = tid / TPR; r < RG; r += RPP) {
+            int m = m0 + rg * RG + r;
+            if (m < M) epi.template operator()<BN>(m, bn, cc, stage + r * LDS_LD);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- staged loop
+constexpr int BK = 64;
+constexpr int CPR = BK / 8;   // 16-byte chunks per tile row
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
-    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, BSrc bsrc,
+    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int GM, BSrc bsrc,
     Epi epi) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int NT = NW * 64;
@@ -198,8 +288,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;   // DMA instructions per wave and tile
     static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads");
-    static_assert(BM % RG == 0 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
-    static_assert(RG * (BN + 4) * 4 <= (BM + BN) * BK * 2, "epilogue stage fits in one pipeline stage");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+    static_assert(32 * (BN + 4) * 4 <= (BM + BN) * BK * 2, "epilogue stage fits in one pipeline stage");
 
     // Two pipeline stages as separate arrays, so that a DMA into one stage is
     // known not to alias the fragment reads of the other.
@@ -208,8 +298,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
-    const int vb = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-    const int bm = vb % tiles_m, bn = vb / tiles_m;   // neighbours share the weight tile
+    int bm, bn;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, GM, &bm, &bn);
     const int m0 = bm * BM;
 
     // One DMA instruction moves 8 tile rows (8 x 128 B).  Lane L fills physical
@@ -309,75 +399,229 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         compute(st0);
         __syncthreads();
     }
-
-    // ---- epilogue: accumulators -> LDS (fp32, RG rows at a time) -> fused store ----
-    float* stage = reinterpret_cast<float*>(st0);
-    constexpr int LDS_LD = BN + 4;
-    constexpr int TPR = BN / 8;           // threads per staged row
-    constexpr int RPP = NT / TPR;         // rows per pass
-#pragma unroll
-    for (int rg = 0; rg < BM / RG; ++rg) {
-        if (rg) __syncthreads();
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int tr = wm0 + i * 32;
-            if (tr / RG == rg) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int r = (tr % RG) + 8 * (v >> 2) + 4 * fk + (v & 3);
-                        stage[r * LDS_LD + wn0 + j * 32 + frow] = acc[i][j][v];
-                    }
-            }
-        }
-        __syncthreads();
-        const int cc = (tid % TPR) * 8;
-        for (int r = tid / TPR; r < RG; r += RPP) {
-            int m = m0 + rg * RG + r;
-            if (m < M) epi.template operator()<BN>(m, bn, cc, stage + r * LDS_LD);
-        }
-    }
+    store_tile<BM, BN, WAVES_M, WAVES_N, 32>(acc, reinterpret_cast<float*>(st0), m0, bn, M, epi);
 }
+
+// ------------------------------------------------------------------ ring loop
+constexpr int BKS = 32;   // K columns per slice
+constexpr int NS = 4;     // ring slots
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
-void launch_gemm_cfg(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, BSrc bsrc, Epi epi,
-                 hipStream_t s) {
-    // N_tiles_cols: number of output columns covered by tiles of BN
-    auto kern = gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, BSrc, Epi>;
-    constexpr int lds = 0;
-    int tiles_m = (M + BM - 1) / BM, tiles_n = (N_tiles_cols + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WAVES_M * WAVES_N * 64), lds, s, A, lda,
-                       M, K, tiles_m, tiles_n, bsrc, epi);
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
+    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int GM, BSrc bsrc,
+    Epi epi) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int A_I = BM / 16 / NW, B_I = BN / 16 / NW;   // DMA instructions per wave and slice
+    constexpr int DPS = A_I + B_I;
+    constexpr int SL = (BM + BN) * BKS;
+    static_assert(BM % (16 * NW) == 0 && BN % (32 * NW) == 0, "tile/waves");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+    static_assert(16 * (BN + 4) * 4 <= SL * 2, "epilogue stage fits in one slot");
+    static_assert(DPS * (NS - 1) < 64, "vmcnt range");
+
+    // One array per ring slot: the compiler then knows that a DMA into one slot
+    // does not alias the fragment reads of another and adds no waits of its own.
+    __shared__ __align__(16) bf16_t sl0[SL];
+    __shared__ __align__(16) bf16_t sl1[SL];
+    __shared__ __align__(16) bf16_t sl2[SL];
+    __shared__ __align__(16) bf16_t sl3[SL];
+    auto slot = [&](int i) -> bf16_t* { return i == 0 ? sl0 : i == 1 ? sl1 : i == 2 ? sl2 : sl3; };
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+    int bm, bn;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, GM, &bm, &bn);
+    const int m0 = bm * BM;
+
+    // One DMA instruction moves 16 slice rows (16 x 64 B).  Lane L fills physical
+    // chunk slot L%4 of row L/4 and fetches the logical chunk slot ^ ((row>>2)&3):
+    // a 16-byte fragment read of 16 consecutive rows then touches every bank once.
+    // Global addresses are a wave-uniform base (advanced along K in scalar
+    // registers) plus a loop-invariant 32-bit lane offset.
+    uint32_t ao[A_I], bo[B_I];
+    const int a_rows = M - m0;
+#pragma unroll
+    for (int i = 0; i < A_I; ++i) {
+        int r = (i * NW + wave) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        r = r < a_rows ? r : a_rows - 1;
+        ao[i] = (uint32_t)((r * lda + c * 8) * 2);
+    }
+#pragma unroll
+    for (int i = 0; i < B_I; ++i) {
+        constexpr int HI = B_I / 2;                       // instructions per half tile
+        const int half = i / HI;
+        int r = ((i % HI) * NW + wave) * 16 + (lane >> 2);   // row within the half
+        const int c = (lane & 3) ^ ((r >> 2) & 3);           // BN/2 is a multiple of 16: same swizzle
+        const int left = bsrc.template rows_left<BN>(bn, half);
+        r = r < left ? r : left - 1;
+        bo[i] = (uint32_t)((r * bsrc.ldb + c * 8) * 2);
+    }
+    const char* abase = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+    const char* bbase0 = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, 0));
+    const char* bbase1 = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, 1));
+    const int wbase = __builtin_amdgcn_readfirstlane(wave) * 16 * BKS;
+    auto scalar_ptr = [](const char* p) -> const char* {   // keeps the base in scalar registers
+        const uint64_t u = reinterpret_cast<uint64_t>(p);
+        const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
+        const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(u >> 32));
+        return reinterpret_cast<const char*>((hi << 32) | lo);
+    };
+    auto dma_slice = [&](bf16_t* s, int sidx) {
+        const int64_t kb = (int64_t)sidx * (BKS * 2);
+        const char* ab = scalar_ptr(abase + kb);
+        const char* bb0 = scalar_ptr(bbase0 + kb);
+        const char* bb1 = scalar_ptr(bbase1 + kb);
+#pragma unroll
+        for (int i = 0; i < A_I; ++i) {
+            asm volatile("" : "+v"(ao[i]));   // keeps the offset a 32-bit register operand of the load
+            dma16(reinterpret_cast<const bf16_t*>(ab + ao[i]), s + i * NW * 16 * BKS + wbase);
+        }
+#pragma unroll
+        for (int i = 0; i < B_I; ++i) {
+            constexpr int HI = B_I / 2;
+            asm volatile("" : "+v"(bo[i]));
+            dma16(reinterpret_cast<const bf16_t*>((i < HI ? bb0 : bb1) + bo[i]),
+                  s + BM * BKS + (i / HI) * (BN / 2) * BKS + (i % HI) * NW * 16 * BKS + wbase);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int frow = lane & 31, fk = lane >> 5;
+    const int fsw = (frow >> 2) & 3;      // rows of a fragment differ by multiples of 32
+    bf16x8 af[2][TM], bfr[2][TN];
+    auto load_frags = [&](const bf16_t* s, int ks, int fb) {
+        const int sl = ((ks * 2 + fk) ^ fsw) << 3;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            af[fb][i] = *reinterpret_cast<const bf16x8*>(s + (wm0 + i * 32 + frow) * BKS + sl);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            bfr[fb][j] = *reinterpret_cast<const bf16x8*>(s + BM * BKS + (wn0 + j * 32 + frow) * BKS + sl);
+    };
+    auto mfmas = [&](int fb) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fb][i], bfr[fb][j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int NF = TM + TN, NM = TM * TN;
+    auto pin_interleave = [&]() {   // issue order: every MFMA followed by one fragment read
+#pragma unroll
+        for (int mm = 0; mm < NM; ++mm) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (mm < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
+
+    // The two 16-column k-steps of a slice alternate between two fragment
+    // register sets, and the stream of k-steps runs on across slice boundaries:
+    // the MFMAs of a slice's second k-step are issued after the barrier that opens
+    // the next slice, so they cover the latency of its first fragment reads.
+    // At a boundary a wave waits until its own loads of the next slice have landed
+    // (vmcnt: only the younger slices may be outstanding) and its fragment reads
+    // of the current slice have returned; after the barrier the slot just read is
+    // free everywhere and is refilled with the slice NS ahead.
+    const int KS = K / BKS;            // K % (BKS * NS) == 0, KS >= NS
+#pragma unroll
+    for (int j = 0; j < NS; ++j) dma_slice(slot(j), j);
+    wait_vm_lds0<DPS * (NS - 1)>();
+    __builtin_amdgcn_s_barrier();
+    load_frags(slot(0), 0, 0);
+    int s0 = 0;
+    for (; s0 + 2 * NS <= KS; s0 += NS) {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            load_frags(slot(j), 1, 1);
+            mfmas(0);
+            pin_interleave();
+            wait_vm_lds0<DPS * (NS - 2)>();
+            __builtin_amdgcn_s_barrier();
+            dma_slice(slot(j), s0 + j + NS);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(slot((j + 1) % NS), 0, 0);
+            mfmas(1);
+            pin_interleave();
+        }
+    }
+    // the last NS slices are in flight or landed: no refills
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+        load_frags(slot(j), 1, 1);
+        mfmas(0);
+        pin_interleave();
+        if (j + 1 < NS) {
+            if (j == 0) wait_vm_lds0<DPS * (NS - 2)>();
+            else if (j == 1) wait_vm_lds0<DPS * (NS - 3)>();
+            else wait_vm_lds0<0>();
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(slot(j + 1), 0, 0);
+            mfmas(1);
+            pin_interleave();
+        } else {
+            mfmas(1);
+        }
+    }
+    __syncthreads();   // every wave has finished reading the ring
+    store_tile<BM, BN, WAVES_M, WAVES_N, 16>(acc, reinterpret_cast<float*>(sl0), m0, bn, M, epi);
 }
 
-// Two tile shapes: 256x256 (8 waves of 128x64, least LDS and L1 traffic per
-// flop, one workgroup per CU) and 128x128 (4 waves of 64x64, two per CU, about
-// 0.88 of the large tile's rate).  A grid runs as a whole number of "rounds" of
-// workgroups, so the shape is chosen per launch to minimise rounds x tile cost.
+// Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
+// workgroup per CU) and 128x128 (4 waves of 64x64, two per CU, measured at 0.6 to
+// 0.9 of the large tile's rate depending on K).  A grid runs as a whole number of "rounds" of workgroups,
+// so the shape is chosen per launch to minimise rounds x tile cost.
 template <class BSrc, class Epi>
-void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, BSrc bsrc, Epi epi,
-                 hipStream_t s) {
+void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int ldb, int gm_big,
+                 BSrc bsrc, Epi epi, hipStream_t s) {
     static const int n_cu = [] {
         int dev = 0, n = 256;
         if (hipGetDevice(&dev) == hipSuccess)
             (void)hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         return n > 0 ? n : 256;
     }();
-    static const char* force = getenv("CC_GEMM_CFG");
+    static const char* force = [] { const char* e = getenv("CC_GEMM_CFG"); return (e && *e) ? e : (const char*)nullptr; }();   // "b" / "s": tile; second char "t": staged loop
+    static const char* force_gm = [] { const char* e = getenv("CC_GEMM_GM"); return (e && *e) ? e : (const char*)nullptr; }();
     auto cost = [&](int bm, int bn, int per_cu, double eff) {
         const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn);
         const long slots = (long)n_cu * per_cu;
         const long rounds = (tiles + slots - 1) / slots;
         return (double)rounds * per_cu * bm * bn / eff;
     };
-    const double cb = cost(256, 256, 1, 1.00), cs = cost(128, 128, 2, 0.88);
+    const double cb = cost(256, 256, 1, 1.00), cs = cost(128, 128, 2, 0.72);
     char pick = cb <= cs ? 'b' : 's';
-    if (force) pick = force[0];
-    if (pick == 'b')
-        launch_gemm_cfg<256, 256, 2, 4>(A, lda, M, N_tiles_cols, K, bsrc, epi, s);
-    else
-        launch_gemm_cfg<128, 128, 2, 2>(A, lda, M, N_tiles_cols, K, bsrc, epi, s);
+    if (force && (force[0] == 'b' || force[0] == 's')) pick = force[0];
+    // ring loop: whole groups of NS slices, 32-bit lane offsets within a tile's rows
+    bool ring = K % (BKS * NS) == 0 && (int64_t)lda * 256 * 2 < (1ll << 31) &&
+                (int64_t)ldb * 256 * 2 < (1ll << 31);
+    if (force && force[0] && force[1] == 't') ring = false;
+    const int bm = pick == 'b' ? 256 : 128;
+    const int tiles_m = (M + bm - 1) / bm, tiles_n = (N_tiles_cols + bm - 1) / bm;
+    int GM = pick == 'b' ? gm_big : 2 * gm_big;
+    if (force_gm) GM = atoi(force_gm);
+    GM = GM < 1 ? 1 : (GM > tiles_m ? tiles_m : GM);
+    const dim3 grid(tiles_m * tiles_n);
+#define CC_LAUNCH(KERN, BM_, WM_, WN_)                                                            \
+    hipLaunchKernelGGL((KERN<BM_, BM_, WM_, WN_, BSrc, Epi>), grid, dim3(WM_ * WN_ * 64), 0, s, A, \
+                       lda, M, K, tiles_m, tiles_n, GM, bsrc, epi)
+    if (pick == 'b') {
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 2, 4);
+        else CC_LAUNCH(gemm_nt_kernel, 256, 2, 4);
+    } else {
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 2, 2);
+        else CC_LAUNCH(gemm_nt_kernel, 128, 2, 2);
+    }
+#undef CC_LAUNCH
 }
 
 }  // namespace
@@ -390,7 +634,7 @@ void cc_launch_qkv(const bf16_t* xn, int M, const int32_t* idx, const bf16_t* w_
     BSingle b{w_qkv, m.d, N};
     EpiQKV e{idx, b_qkv, rope, m.H_q, m.H_kv, m.d_h, N, q_out,
              (bf16_t*)kv.K, (bf16_t*)kv.V, kv.stride_token, kv.stride_head};
-    launch_gemm(xn, m.d, M, N, m.d, b, e, s);
+    launch_gemm(xn, m.d, M, N, m.d, m.d, 4, b, e, s);
 }
 
 void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hidden,
@@ -399,7 +643,7 @@ void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hi
     const int K = m.H_q * m.d_h;
     BSingle b{w_o, K, m.d};
     EpiOProj e{hidden, gather_idx, m.d, y};
-    launch_gemm(o, K, M, m.d, K, b, e, s);
+    launch_gemm(o, K, M, m.d, K, K, 4, b, e, s);
 }
 
 void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16_t* w_up,
@@ -408,7 +652,7 @@ void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16
     BDual b{w_gate, w_up, m.d, m.f};
     EpiGateUp e{m.f, act};
     // each 128-column tile holds 64 gate + 64 up columns: 2*f tile columns in total
-    launch_gemm(mn, m.d, M, 2 * m.f, m.d, b, e, s);
+    launch_gemm(mn, m.d, M, 2 * m.f, m.d, m.d, 4, b, e, s);
 }
 
 void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float* y,
@@ -416,5 +660,5 @@ void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float*
     if (M <= 0) return;
     BSingle b{w_down, m.f, m.d};
     EpiDown e{y, m.d, out};
-    launch_gemm(act, m.f, M, m.d, m.f, b, e, s);
+    launch_gemm(act, m.f, M, m.d, m.f, m.f, 8, b, e, s);
 }
