@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+CALIB_COPY_BYTES = 1 << 30
+# HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
+# by the calibration copy); written by paper_2510_10129_amd.rocprof_summary from a profiled run
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "c3_stack_hbm_traffic_pmc.txt")
 
 
 def parse():
@@ -37,6 +41,8 @@ def parse():
     ap.add_argument("--exact-idx", action="store_true",
                     help="time the layers on a hand-built set of exactly recomp%% tokens instead of select's output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch one copy of 1 GiB through cc_calib_copy (for counter calibration under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -59,7 +65,7 @@ def algorithmic_work(model, idx_host, N, Q_a, T):
     }
 
 
-def cpu_baseline(wl, model, recomp_bp, n_rows=6):
+def cpu_baseline(wl, model, recomp_bp, n_rows=32):
     """The oracle as it stands, on the host cores: selection in full; one layer with
     the K/V update (steps 1-4) for all M rows and attention + the rest of the layer
     (steps 5-7) for a few sampled rows, scaled to M rows."""
@@ -154,6 +160,12 @@ def main():
 
     for _ in range(a.warmup):
         M = step()
+    if a.calib_copy:
+        src = torch.zeros(CALIB_COPY_BYTES, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        ctx.calib_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(a.steps):
@@ -188,6 +200,10 @@ def main():
             ach = amount / (avg_ms * 1e-3) / 1e9
             kernels[name] = {"avg_ms": round(avg_ms, 5), "launches_per_step": cnt // a.steps, "bound": bound,
                              "achieved_GBs": round(ach, 1), "frac": round(ach / PEAK_HBM_GBS, 4)}
+    from paper_2510_10129_amd.rocprof_summary import read_traffic
+    measured = read_traffic(TRAFFIC_SUMMARY) if a.workload == "C3" and not a.exact_idx else {}
+    for name in kernels:
+        kernels[name]["traffic_bytes"] = measured.get(name)
     dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_per_step"])
     kd = kernels[dom]
     roofline = {
@@ -195,7 +211,7 @@ def main():
         "achieved": kd.get("achieved_TFLOPs", kd.get("achieved_GBs")),
         "peak": PEAK_BF16_TFLOPS if kd["bound"] == "mfma" else PEAK_HBM_GBS,
         "unit": "TFLOP/s" if kd["bound"] == "mfma" else "GB/s",
-        "frac": kd["frac"], "traffic": None, "avg_ms": kd["avg_ms"],
+        "frac": kd["frac"], "traffic": kd["traffic_bytes"], "avg_ms": kd["avg_ms"],
     }
     layer_flops = sum(v for k, (b, v) in work.items() if b == "mfma")
     ms_per_layer = dt * 1e3 / L

@@ -185,6 +185,13 @@ cc_status cc_profile_enable(cc_ctx* ctx, int32_t on);
  * host) since the last read, and resets them. */
 cc_status cc_profile_read(cc_ctx* ctx, float* ms, int32_t* count);
 
+/* Measurement support, not a step of the method: copies `bytes` (a multiple of 16,
+ * both pointers dev and 16-byte aligned, buffers not overlapping) with a plain
+ * 16-bytes-per-lane kernel.  Hardware counters of HBM traffic (bytes fetched / written
+ * per dispatch) are calibrated against this kernel, whose traffic is known: `bytes`
+ * read and `bytes` written. */
+cc_status cc_calib_copy(cc_ctx* ctx, void* dst, const void* src, int64_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ EXPORTS = (
     "cc_create", "cc_destroy", "cc_set_stream", "cc_last_error", "cc_select",
     "cc_step_column_scores", "cc_recompute_layer", "cc_step_gather_rmsnorm",
     "cc_step_qkv_rope_scatter", "cc_step_sparse_attention", "cc_step_oproj_residual",
-    "cc_step_mlp", "cc_profile_enable", "cc_profile_read",
+    "cc_step_mlp", "cc_profile_enable", "cc_profile_read", "cc_calib_copy",
 )
 
 
@@ -85,6 +85,7 @@ def load_library() -> C.CDLL:
     lib.cc_step_sparse_attention.argtypes = [vp, vp, i32, vp, C.POINTER(_KV), vp, i32]
     lib.cc_step_oproj_residual.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp]
     lib.cc_step_mlp.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.cc_calib_copy.argtypes = [vp, vp, vp, i64]
     lib.cc_profile_enable.argtypes = [vp, i32]
     lib.cc_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     for name in EXPORTS:
@@ -217,6 +218,11 @@ class Context:
         self._check(self._lib.cc_step_mlp(self._h, y.data_ptr(), M, w_post_norm.data_ptr(),
                                           w_gate.data_ptr(), w_up.data_ptr(), w_down.data_ptr(),
                                           out.data_ptr()))
+
+    # ---- measurement support ----
+    def calib_copy(self, dst, src):
+        self._check(self._lib.cc_calib_copy(self._h, dst.data_ptr(), src.data_ptr(),
+                                            src.numel() * src.element_size()))
 
     # ---- timing ----
     def profile_enable(self, on: bool):

@@ -343,6 +343,16 @@ cc_status cc_recompute_layer(cc_ctx* c, const void* hidden, int64_t rows, const 
     return cc_step_mlp(c, c->y, M, w->w_post_norm, w->w_gate, w->w_up, w->w_down, out);
 }
 
+cc_status cc_calib_copy(cc_ctx* c, void* dst, const void* src, int64_t bytes) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!dst || !src) return fail(c, CC_ERR_NULL, "dst and src must not be NULL");
+    if (bytes < 0 || bytes % 16 || !aligned16(dst) || !aligned16(src))
+        return fail(c, CC_ERR_SHAPE, "bytes must be a non-negative multiple of 16, pointers 16-byte aligned");
+    cc_launch_copy(dst, src, bytes, c->stream);
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
 cc_status cc_profile_enable(cc_ctx* c, int32_t on) {
     if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
     c->prof = on != 0;

@@ -58,6 +58,7 @@ struct cc_prof_scope {
 };
 
 // ---- kernel launchers (each only enqueues on `s`) ----
+void cc_launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t s);
 void cc_launch_rope_table(float2* table, int n_pos, int d_h, double base, hipStream_t s);
 void cc_launch_colsum(const float* attn, int Q_a, int T, int64_t ld, float* score, hipStream_t s);
 void cc_launch_select(const float* score, int T, int k, int window, int tau, int grouping,

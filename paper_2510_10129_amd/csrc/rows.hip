@@ -125,3 +125,20 @@ void cc_launch_rope_table(float2* table, int n_pos, int d_h, double base, hipStr
     hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, table,
                        n_pos, half, log2(base));
 }
+
+// Plain copy, 16 bytes per lane, grid-stride: the known-traffic kernel that the
+// HBM byte counters are calibrated against.
+__global__ __launch_bounds__(256) void calib_copy_kernel(u32x4* __restrict__ dst,
+                                                         const u32x4* __restrict__ src, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        dst[i] = src[i];
+}
+
+void cc_launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t s) {
+    const int64_t n = bytes / 16;
+    if (n <= 0) return;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(calib_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (u32x4*)dst,
+                       (const u32x4*)src, n);
+}
