@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--exact-idx", action="store_true",
                     help="time the layers on a hand-built set of exactly recomp%% tokens instead of select's output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hbm-extra", action="store_true",
+                    help="skip timing the HBM-bound kernels at the C5 shape (where they run long enough to measure)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one copy of 1 GiB through cc_calib_copy (for counter calibration under rocprofv3 --pmc)")
     return ap.parse_args()
@@ -63,6 +65,43 @@ def algorithmic_work(model, idx_host, N, Q_a, T):
         "gate_up": ("mfma", 4 * M * d * f),
         "down": ("mfma", 2 * M * f * d),
     }
+
+
+def hbm_kernels_c5(dev, reps=20):
+    """The HBM-bound kernels alone at the Llama-3-70B-shaped config (C5): at C3 they move
+    8-100 MB and finish in 5-20 us, next to launch overheads; here they run long enough for
+    the event timing to show the bandwidth they reach."""
+    import torch
+    import paper_2510_10129_amd as cc
+    from workloads import CONFIGS, gen
+    wl = CONFIGS["C5"]
+    m = wl.model
+    ctx = cc.Context.for_model(m, N_cap=64, M_cap=64, T_cap=64)     # stage calls use caller buffers only
+    idx_h = gen.exact_ratio_idx(wl, 2000)
+    M = len(idx_h)
+    idx = torch.from_numpy(idx_h).to(dev)
+    A = torch.rand((wl.Q_a, wl.T), dtype=torch.float32, device=dev)
+    score = torch.empty(wl.T, dtype=torch.float32, device=dev)
+    hidden = torch.randn((wl.N, m.d), dtype=torch.float32, device=dev).to(torch.bfloat16)
+    w = torch.ones(m.d, dtype=torch.bfloat16, device=dev)
+    xn = torch.empty((M, m.d), dtype=torch.bfloat16, device=dev)
+    ctx.profile_enable(True)
+    for it in range(reps + 2):
+        if it == 2:
+            ctx.profile_read()
+        ctx.step_column_scores(A, score)
+        ctx.step_gather_rmsnorm(hidden, idx, M, w, xn)
+    prof = ctx.profile_read()
+    ctx.close()
+    work = {"colsum": wl.Q_a * wl.T * 4 + wl.T * 4, "gather_norm": M * m.d * 2 * 2}
+    out = {"shape": f"C5: A[{wl.Q_a},{wl.T}] fp32; gather {M} of {wl.N} rows, d={m.d}"}
+    for k, nbytes in work.items():
+        ms, cnt = prof[k]
+        avg = ms / cnt
+        gbs = nbytes / (avg * 1e-3) / 1e9
+        out[k] = {"avg_ms": round(avg, 5), "bytes": nbytes, "achieved_GBs": round(gbs, 1),
+                  "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    return out
 
 
 def cpu_baseline(wl, model, recomp_bp, n_rows=32):
@@ -231,9 +270,13 @@ def main():
         "ms_per_step_with_events": dt_ev * 1e3,
         "roofline": roofline, "kernels": kernels,
     }
+    ctx.close()
+    if not a.no_hbm_extra:
+        del weights, caches, bufs, X
+        torch.cuda.empty_cache()
+        res["hbm_kernels_at_C5_shape"] = hbm_kernels_c5(dev)
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, model, a.recomp_bp)
-    ctx.close()
     print(json.dumps(res))
 
 

@@ -90,14 +90,14 @@ struct EpiQKV {
     bf16_t* V;
     int64_t st, sh;
     template <int BN>
-    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow) const {
+    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow, int swz) const {
         const int n = bn * BN + cc;
         if (n >= N) return;
         const int head = n / d_h, c = n - head * d_h, half = d_h >> 1;
         const int pos = idx[m];
         float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = crow[cc + u];
+        for (int u = 0; u < 8; ++u) v[u] = crow[(cc ^ swz) + u];
         if (bias) {
             bf16x8 b = *reinterpret_cast<const bf16x8*>(bias + n);
 #pragma unroll
@@ -110,7 +110,7 @@ struct EpiQKV {
             const int j = lo ? c : c - half;
             float p[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) p[u] = crow[pcc + u];
+            for (int u = 0; u < 8; ++u) p[u] = crow[(pcc ^ swz) + u];
             if (bias) {
                 bf16x8 b = *reinterpret_cast<const bf16x8*>(bias + pn);
 #pragma unroll
@@ -140,16 +140,17 @@ struct EpiOProj {
     int d;
     float* y;
     template <int BN>
-    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow) const {
+    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow, int swz) const {
         const int n = bn * BN + cc;
         if (n >= d) return;
         const int64_t src = gather_idx ? (int64_t)gather_idx[m] : (int64_t)m;
         bf16x8 x = *reinterpret_cast<const bf16x8*>(hidden + src * d + n);
+        const float* cr = crow + (cc ^ swz);
         f32x4 a, b;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            a[u] = crow[cc + u] + (float)x[u];
-            b[u] = crow[cc + 4 + u] + (float)x[4 + u];
+            a[u] = cr[u] + (float)x[u];
+            b[u] = cr[4 + u] + (float)x[4 + u];
         }
         f32x4* dst = reinterpret_cast<f32x4*>(y + (int64_t)m * d + n);
         dst[0] = a;
@@ -161,7 +162,7 @@ struct EpiGateUp {
     int f;
     bf16_t* act;
     template <int BN>
-    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow) const {
+    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow, int swz) const {
         constexpr int H = BN / 2;
         if (cc >= H) return;
         const int n = bn * H + cc;
@@ -169,7 +170,7 @@ struct EpiGateUp {
         float v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            float g = crow[cc + u], up = crow[cc + H + u];
+            float g = crow[(cc ^ swz) + u], up = crow[((cc + H) ^ swz) + u];
             v[u] = g / (1.0f + __expf(-g)) * up;
         }
         store_bf16x8(act + (int64_t)m * f + n, v);
@@ -181,16 +182,17 @@ struct EpiDown {
     int d;
     bf16_t* out;
     template <int BN>
-    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow) const {
+    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow, int swz) const {
         const int n = bn * BN + cc;
         if (n >= d) return;
         const f32x4* r = reinterpret_cast<const f32x4*>(y + (int64_t)m * d + n);
         f32x4 a = r[0], b = r[1];
+        const float* cr = crow + (cc ^ swz);
         float v[8];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            v[u] = crow[cc + u] + a[u];
-            v[4 + u] = crow[cc + 4 + u] + b[u];
+            v[u] = cr[u] + a[u];
+            v[4 + u] = cr[4 + u] + b[u];
         }
         store_bf16x8(out + (int64_t)m * d + n, v);
     }
@@ -269,7 +271,62 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[BM / WAVES_M / 32][BN /
         const int cc = (tid % TPR) * 8;
         for (int r = tid / TPR; r < RG; r += RPP) {
             int m = m0 + rg * RG + r;
-            if (m < M) epi.template operator()<BN>(m, bn, cc, stage + r * LDS_LD);
+            if (m < M) epi.template operator()<BN>(m, bn, cc, stage + r * LDS_LD, 0);
+        }
+    }
+}
+
+// Ring-loop epilogue.  After the K loop the four ring slots are free; each holds
+// one 32-row group of the tile as fp32 [32][BN] (exactly one slot), so a 256-row
+// tile leaves in two phases of four groups with two barriers per phase, and a
+// thread's functor calls of a phase are independent (their global loads overlap).
+// Column c of staged row r sits at c ^ 32*((r>>2)&1): the two half-waves of an
+// accumulator store (rows r and r+4) then hit disjoint banks, and 8-column
+// chunks stay contiguous for the functors.
+template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+__device__ __forceinline__ void store_tile_ring(f32x16 (&acc)[BM / WAVES_M / 32][BN / WAVES_N / 32],
+                                                float* s0, float* s1, float* s2, float* s3, int m0,
+                                                int bn, int M, const Epi& epi) {
+    constexpr int NT = WAVES_M * WAVES_N * 64;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int IPP = 4 / WAVES_M;      // accumulator row blocks per wave and phase
+    constexpr int PHASES = TM / IPP;
+    constexpr int TPR = BN / 8;           // threads per staged row
+    constexpr int RPP = NT / TPR;         // rows per pass
+    static_assert(4 % WAVES_M == 0 && TM % IPP == 0 && 32 % RPP == 0, "epilogue shape");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WAVES_M, wn0 = (wave / WAVES_M) * WN;
+    const int frow = lane & 31, fk = lane >> 5;
+    auto stage = [&](int q) -> float* { return q == 0 ? s0 : q == 1 ? s1 : q == 2 ? s2 : s3; };
+#pragma unroll
+    for (int p = 0; p < PHASES; ++p) {
+        if (p) __syncthreads();
+        // register v of a 32x32 accumulator tile holds tile row r = 8*(v>>2) + 4*fk + (v&3);
+        // (r>>2)&1 == fk
+#pragma unroll
+        for (int ii = 0; ii < IPP; ++ii) {
+            const int i = p * IPP + ii;
+            float* st = stage(wm * IPP + ii);     // slot q holds wave-row q / IPP, block q % IPP
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = 8 * (v >> 2) + 4 * fk + (v & 3);
+                    st[r * BN + ((wn0 + j * 32 + frow) ^ (fk << 5))] = acc[i][j][v];
+                }
+        }
+        __syncthreads();
+        const int cc = (tid % TPR) * 8;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row0 = (q / IPP) * WM + (p * IPP + q % IPP) * 32;   // tile row of the slot's first row
+#pragma unroll
+            for (int k = 0; k < 32 / RPP; ++k) {
+                const int r = tid / TPR + k * RPP;
+                const int m = m0 + row0 + r;
+                if (m < M) epi.template operator()<BN>(m, bn, cc, stage(q) + r * BN, ((r >> 2) & 1) << 5);
+            }
         }
     }
 }
@@ -418,7 +475,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     constexpr int SL = (BM + BN) * BKS;
     static_assert(BM % (16 * NW) == 0 && BN % (32 * NW) == 0, "tile/waves");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
-    static_assert(16 * (BN + 4) * 4 <= SL * 2, "epilogue stage fits in one slot");
+    static_assert(32 * BN * 4 <= SL * 2, "a 32-row fp32 group fits in one slot");
     static_assert(DPS * (NS - 1) < 64, "vmcnt range");
 
     // One array per ring slot: the compiler then knows that a DMA into one slot
@@ -574,7 +631,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
         }
     }
     __syncthreads();   // every wave has finished reading the ring
-    store_tile<BM, BN, WAVES_M, WAVES_N, 16>(acc, reinterpret_cast<float*>(sl0), m0, bn, M, epi);
+    store_tile_ring<BM, BN, WAVES_M, WAVES_N>(acc, reinterpret_cast<float*>(sl0), reinterpret_cast<float*>(sl1),
+                                              reinterpret_cast<float*>(sl2), reinterpret_cast<float*>(sl3),
+                                              m0, bn, M, epi);
 }
 
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one

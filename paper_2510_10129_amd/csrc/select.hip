@@ -5,32 +5,61 @@
 
 // ----------------------------------------------------------------------------
 // Importance score per chunk token: sum of the query->chunk attention block
-// over its query rows (Section 4.2).  One lane owns one column and adds the
-// rows in ascending order with a single fp32 accumulator, so the result is
-// the same bit pattern on every run and on any host that adds in that order.
-// Loads of 32 rows are issued together (the kernel is bound by load latency,
-// not by adds); a wave reads 256 contiguous bytes per row.
+// over its query rows (Section 4.2).  Every column has ONE fp32 accumulator
+// and its rows are added in ascending order, so the result is the same bit
+// pattern on every run and on any host that adds in that order.
+//
+// The adds are cheap; the kernel lives on bytes in flight.  A workgroup of four
+// waves owns 64 columns.  Rows are taken 64 at a time: wave w issues the loads
+// of rows 16w .. 16w+15 of the chunk together (lane = column, 256 contiguous
+// bytes per row and wave) and parks them in LDS; wave 0 then walks the 64
+// rows of its column in order.  32 KB of LDS per workgroup: five workgroups
+// (80 KB of loads in flight) per CU.  Two LDS buffers let the loads of the next chunk
+// start while the sums of this one are taken.
 // ----------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void colsum_kernel(const float* __restrict__ attn, int Q_a, int T,
-                                                    int64_t ld, float* __restrict__ score) {
-    int t = blockIdx.x * 64 + threadIdx.x;
-    if (t >= T) return;
-    const float* p = attn + t;
+#define CS_ROWS 64
+#define CS_RPW (CS_ROWS / 4)   // rows per wave and chunk
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ attn, int Q_a, int T,
+                                                     int64_t ld, float* __restrict__ score) {
+    __shared__ float tile[2][CS_ROWS][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x * 64 + lane;
+    const bool col_ok = t < T;
+    const float* p = attn + (col_ok ? t : 0);
     float acc = 0.0f;
-    int q = 0;
-    for (; q + 32 <= Q_a; q += 32) {
-        float v[32];
+    const int n_chunks = (Q_a + CS_ROWS - 1) / CS_ROWS;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int q0 = c * CS_ROWS + wave * CS_RPW;
+        float (*buf)[64] = tile[c & 1];
+        float v[CS_RPW];
 #pragma unroll
-        for (int u = 0; u < 32; ++u) v[u] = __builtin_nontemporal_load(p + (int64_t)(q + u) * ld);
+        for (int u = 0; u < CS_RPW; ++u) {      // rows past the end re-read the last row and are not summed
+            const int q = min(q0 + u, Q_a - 1);
+            v[u] = __builtin_nontemporal_load(p + (int64_t)q * ld);
+        }
 #pragma unroll
-        for (int u = 0; u < 32; ++u) acc = acc + v[u];
+        for (int u = 0; u < CS_RPW; ++u) buf[wave * CS_RPW + u][lane] = v[u];
+        // the buffer written now was last read two chunks ago; one barrier per chunk
+        // orders both that reuse and this hand-over
+        __syncthreads();
+        if (wave == 0) {
+            const int rows = min(CS_ROWS, Q_a - c * CS_ROWS);
+            int r = 0;
+            for (; r + 8 <= rows; r += 8) {
+                float x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = buf[r + u][lane];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc = acc + x[u];
+            }
+            for (; r < rows; ++r) acc = acc + buf[r][lane];
+        }
     }
-    for (; q < Q_a; ++q) acc = acc + p[(int64_t)q * ld];
-    score[t] = acc;
+    if (wave == 0 && col_ok) score[t] = acc;
 }
 
 void cc_launch_colsum(const float* attn, int Q_a, int T, int64_t ld, float* score, hipStream_t s) {
-    hipLaunchKernelGGL(colsum_kernel, dim3((T + 63) / 64), dim3(64), 0, s, attn, Q_a, T, ld, score);
+    hipLaunchKernelGGL(colsum_kernel, dim3((T + 63) / 64), dim3(256), 0, s, attn, Q_a, T, ld, score);
 }
 
 // ----------------------------------------------------------------------------
