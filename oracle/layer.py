@@ -85,6 +85,21 @@ def qkv_rows(x: np.ndarray, weights, model, pos: np.ndarray):
     return rope_rotate(q, pos, model.rope_base), rope_rotate(k, pos, model.rope_base), v
 
 
+def kv_rows(x: np.ndarray, weights, model, pos: np.ndarray):
+    """Steps 1-3 restricted to the key and value heads (the rows of W_qkv below the
+    query heads): (k [M,H_kv,d_h] rotated, v [M,H_kv,d_h]) in fp64.  Same numbers as
+    the k and v of qkv_rows; used where the queries of most rows are not needed."""
+    M = x.shape[0]
+    nq, nk = model.H_q * model.d_h, model.H_kv * model.d_h
+    n = rmsnorm(x, _w(weights, "w_in_norm"), model.rms_eps)
+    kv = n @ bf16.bits_to_f64(weights["w_qkv"][nq:]).T
+    if weights.get("b_qkv") is not None:
+        kv = kv + bf16.bits_to_f64(weights["b_qkv"][nq:])
+    k = kv[:, :nk].reshape(M, model.H_kv, model.d_h)
+    v = kv[:, nk:].reshape(M, model.H_kv, model.d_h)
+    return rope_rotate(k, pos, model.rope_base), v
+
+
 def attend_row(q_row: np.ndarray, K: np.ndarray, V: np.ndarray, p: int, g: int):
     """Causal GQA attention of one query row (all heads) at position p over
     cache slots 0..p.  q_row [H_q, d_h]; K, V fp64 [N, H_kv, d_h].
@@ -103,7 +118,8 @@ def attend_row(q_row: np.ndarray, K: np.ndarray, V: np.ndarray, p: int, g: int):
 def recompute_layer(hidden_bits: np.ndarray, gather_idx: Optional[np.ndarray],
                     K_bits: np.ndarray, V_bits: np.ndarray, idx: np.ndarray,
                     weights: Dict[str, np.ndarray], model,
-                    rows: Optional[Sequence[int]] = None) -> LayerResult:
+                    rows: Optional[Sequence[int]] = None,
+                    q_for_rows_only: bool = False) -> LayerResult:
     """Selective recompute of one layer.
 
     hidden_bits : bf16 bits [rows_in, d]; row gather_idx[i] (or row i when
@@ -114,13 +130,21 @@ def recompute_layer(hidden_bits: np.ndarray, gather_idx: Optional[np.ndarray],
     rows        : evaluate attention and the rest of the layer only for these
                   of the M rows (they are independent once the cache is
                   updated); None = all.
+    q_for_rows_only : project queries only for `rows` (keys and values are still
+                  computed for all M rows); q_rot then holds zeros elsewhere.
     """
     idx = np.asarray(idx, dtype=np.int64)
     M = idx.shape[0]
     g = model.g
     src = np.arange(M) if gather_idx is None else np.asarray(gather_idx, dtype=np.int64)
     x = bf16.bits_to_f64(hidden_bits[src])                              # step 1: gather
-    q, k, v = qkv_rows(x, weights, model, idx)                          # steps 1-3
+    if q_for_rows_only and rows is not None:
+        k, v = kv_rows(x, weights, model, idx)                          # steps 1-3, k and v
+        rsel = np.asarray(rows, dtype=np.int64)
+        q = np.zeros((M, model.H_q, model.d_h))
+        q[rsel] = qkv_rows(x[rsel], weights, model, idx[rsel])[0]       # steps 1-3, q of the sample
+    else:
+        q, k, v = qkv_rows(x, weights, model, idx)                      # steps 1-3
     K_new, V_new = K_bits.copy(), V_bits.copy()
     K_new[idx] = bf16.f64_to_bits(k)                                    # step 4: overwrite
     V_new[idx] = bf16.f64_to_bits(v)

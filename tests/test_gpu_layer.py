@@ -323,3 +323,45 @@ def test_llama8b_layer_4k_sampled_rows(bp):
 def test_llama8b_layer_16k_bench_shape_sampled_rows():
     """The shape and launch configuration bench.py times (one layer of it)."""
     _sampled_layer_case("C3", 2000, 16, 7)
+
+
+def _device_drawn_layer_case(name, bp, n_rows, seed):
+    """One layer at a config's full size with inputs drawn on the device (torch's
+    generator; the host streams would take minutes at these sizes) and copied to the
+    host for the oracle, which projects keys and values for every recomputed row and
+    evaluates attention and the rest of the layer for a sample of rows."""
+    from workloads import gen_device
+    wl = CONFIGS[name]
+    model = replace(wl.model, n_layers=1)
+    dev = torch.device(DEV)
+    wd = gen_device.layer_weights(model, 0, wl.seed, dev)
+    hid = gen_device.hidden(wl, dev)
+    Kd, Vd = gen_device.cache(wl, 0, dev)
+    w = {k: (None if v is None else host_bits(v)) for k, v in wd.items()}
+    xg, Ks, Vs = host_bits(hid), host_bits(Kd), host_bits(Vd)
+    idx = gen.exact_ratio_idx(wl, bp)
+    M = len(idx)
+    rows = np.sort(np.random.default_rng(seed).choice(M, size=n_rows, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    ctx = _ctx(model, wl.N, M)
+    out = torch.full((M, model.d), float("nan"), dtype=torch.bfloat16, device=dev)
+    didx = dev_i32(idx)
+    ctx.recompute_layer(hid, didx, cc.KVLayer(Kd, Vd), didx, M, cc.LayerWeights(**wd), out,
+                        _lib.FLAG_CHECK_IDX)
+    torch.cuda.synchronize()
+    got = dict(out=host_bits(out), K=host_bits(Kd), V=host_bits(Vd))
+    ctx.close()
+    del wd, hid, Kd, Vd, out
+    torch.cuda.empty_cache()
+    ref = layer.recompute_layer(xg, idx, Ks, Vs, idx, w, model, rows=rows, q_for_rows_only=True)
+    _assert_layer(got, ref, Ks, Vs, idx, f"{name}@{bp // 100}% M={M}")
+
+
+def test_qwen7b_layer_29k_ragged_chunks_sampled_rows():
+    """C4: 28 q / 4 kv heads (groups of 7), QKV bias, chunk lengths U[256,1536]."""
+    _device_drawn_layer_case("C4", 2000, 12, 11)
+
+
+def test_llama70b_layer_64k_sampled_rows():
+    """C5: d = 8192, 64 q / 8 kv heads, 64k context."""
+    _device_drawn_layer_case("C5", 2000, 8, 12)

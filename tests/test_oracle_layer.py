@@ -315,3 +315,22 @@ def test_tiny_config_fixture_shapes():
     assert len(idx) == 204 + wl.Q and (np.diff(idx) > 0).all()
     r = layer.recompute_layer(xg, idx, Ks, Vs, idx, w, wl.model, rows=[0, 100, len(idx) - 1])
     assert np.allclose(r.row_sums, 1.0, atol=1e-12) and np.isfinite(r.out).all()
+
+
+def test_kv_only_projection_equals_full_projection():
+    """kv_rows / q_for_rows_only are the same numbers as the full projection."""
+    model = ModelShape(128, 4, 2, 32, 64, 1e4, 1e-5, True, 1)
+    w = gen.layer_weights(model, 0, seed=31)
+    r = np.random.default_rng(3)
+    N = 40
+    xb = gen.f32_to_bf16_bits(r.standard_normal((N, model.d)).astype(np.float32))
+    Kb = gen.f32_to_bf16_bits(r.standard_normal((N, model.H_kv, model.d_h)).astype(np.float32))
+    Vb = gen.f32_to_bf16_bits(r.standard_normal((N, model.H_kv, model.d_h)).astype(np.float32))
+    idx = np.array([2, 3, 9, 17, 18, 39])
+    rows = np.array([1, 4, 5])
+    full = layer.recompute_layer(xb, idx, Kb, Vb, idx, w, model, rows=rows)
+    part = layer.recompute_layer(xb, idx, Kb, Vb, idx, w, model, rows=rows, q_for_rows_only=True)
+    assert np.array_equal(full.K_bits, part.K_bits) and np.array_equal(full.V_bits, part.V_bits)
+    np.testing.assert_allclose(part.k_new, full.k_new, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(part.out, full.out, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(part.q_rot[rows], full.q_rot[rows], rtol=0, atol=1e-12)
