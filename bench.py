@@ -85,16 +85,31 @@ def hbm_kernels_c5(dev, reps=20):
     hidden = torch.randn((wl.N, m.d), dtype=torch.float32, device=dev).to(torch.bfloat16)
     w = torch.ones(m.d, dtype=torch.bfloat16, device=dev)
     xn = torch.empty((M, m.d), dtype=torch.bfloat16, device=dev)
+    # per-chunk caches behind the prefix and the global cache they are assembled into
+    ctx_a = cc.Context.for_model(m, N_cap=wl.N, M_cap=64, T_cap=64)
+    row = (m.H_kv, m.d_h)
+    cK = [torch.randn((wl.P + L,) + row, dtype=torch.float32, device=dev).to(torch.bfloat16) for L in wl.chunk_lens]
+    cV = [torch.randn((wl.P + L,) + row, dtype=torch.float32, device=dev).to(torch.bfloat16) for L in wl.chunk_lens]
+    dst = cc.KVLayer(torch.empty((wl.N,) + row, dtype=torch.bfloat16, device=dev),
+                     torch.empty((wl.N,) + row, dtype=torch.bfloat16, device=dev))
     ctx.profile_enable(True)
+    ctx_a.profile_enable(True)
     for it in range(reps + 2):
         if it == 2:
             ctx.profile_read()
+            ctx_a.profile_read()
         ctx.step_column_scores(A, score)
         ctx.step_gather_rmsnorm(hidden, idx, M, w, xn)
+        ctx_a.assemble_cache(cK, cV, wl.P, wl.Q, dst)
     prof = ctx.profile_read()
+    prof["assemble"] = ctx_a.profile_read()["assemble"]
     ctx.close()
-    work = {"colsum": wl.Q_a * wl.T * 4 + wl.T * 4, "gather_norm": M * m.d * 2 * 2}
-    out = {"shape": f"C5: A[{wl.Q_a},{wl.T}] fp32; gather {M} of {wl.N} rows, d={m.d}"}
+    ctx_a.close()
+    row_bytes = m.H_kv * m.d_h * 2
+    work = {"colsum": wl.Q_a * wl.T * 4 + wl.T * 4, "gather_norm": M * m.d * 2 * 2,
+            "assemble": 2 * row_bytes * ((wl.P + wl.T) + wl.N)}
+    out = {"shape": f"C5: A[{wl.Q_a},{wl.T}] fp32; gather {M} of {wl.N} rows, d={m.d}; "
+                    f"assemble {len(wl.chunk_lens)} chunk caches into [{wl.N},{m.H_kv},{m.d_h}] K and V"}
     for k, nbytes in work.items():
         ms, cnt = prof[k]
         avg = ms / cnt

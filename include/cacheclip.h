@@ -173,10 +173,35 @@ cc_status cc_step_oproj_residual(cc_ctx* ctx, const void* o, int32_t M, const vo
 cc_status cc_step_mlp(cc_ctx* ctx, const float* y, int32_t M, const void* w_post_norm,
                       const void* w_gate, const void* w_up, const void* w_down, void* out);
 
+/*
+ * Online cache assembly (Section 4.1): the per-chunk caches, each precomputed alone
+ * behind the shared prefix at local positions 0 .. P+len-1, are concatenated into one
+ * layer's global cache with a single copy of the prefix and re-numbered positions.
+ *   chunks   host array of n_chunks descriptors (read during the call only).  K and V
+ *            are dev bf16 [P + len, H_kv, d_h]; element (t, h, c) is at
+ *            t*stride_token + h*stride_head + c (strides in elements, shared by all
+ *            chunks, multiples of 8; pointers 16-byte aligned).
+ *   dst rows 0 .. P-1               <- rows 0 .. P-1 of chunk 0 (K and V as stored)
+ *   dst row  P + start_c + t        <- row P + t of chunk c, start_c = len_0 + .. + len_{c-1}:
+ *            V copied; K turned by start_c more positions (pair (j, j + d_h/2) by the
+ *            angle start_c * base^(-2j/d_h), fp32, rounded to bf16 nearest-even), which
+ *            moves it from local position P + t to global position P + start_c + t.
+ *   dst rows P + T .. P + T + n_tail - 1 (the user-query slots) <- zeros.
+ * Requires P >= 0, every len >= 1, P + T + n_tail <= dst->N.  dst must not overlap a chunk.
+ */
+typedef struct cc_chunk_kv {
+    const void* K;
+    const void* V;
+    int32_t len;
+} cc_chunk_kv;
+cc_status cc_assemble_cache(cc_ctx* ctx, const cc_chunk_kv* chunks, int32_t n_chunks, int32_t P,
+                            int64_t stride_token, int64_t stride_head, int32_t n_tail,
+                            const cc_kv_layer* dst);
+
 /* ---- timing of the library's own kernels on its stream ---- */
 enum {
     CC_K_COLSUM = 0, CC_K_SELECT, CC_K_GATHER_NORM, CC_K_QKV, CC_K_ATTN, CC_K_OPROJ,
-    CC_K_POST_NORM, CC_K_GATE_UP, CC_K_DOWN, CC_K_COUNT
+    CC_K_POST_NORM, CC_K_GATE_UP, CC_K_DOWN, CC_K_ASSEMBLE, CC_K_COUNT
 };
 /* While enabled, every kernel launch is bracketed by HIP events on the stream. */
 cc_status cc_profile_enable(cc_ctx* ctx, int32_t on);

@@ -15,13 +15,14 @@ _LIB_NAME = "libcacheclip.so"
 CC_OK = 0
 CC_ERR_NULL, CC_ERR_SHAPE, CC_ERR_IDX, CC_ERR_WORKSPACE, CC_ERR_HIP = -1, -2, -3, -4, -5
 FLAG_NO_GROUPING, FLAG_CHECK_IDX = 1, 2
-K_NAMES = ("colsum", "select", "gather_norm", "qkv", "attn", "oproj", "post_norm", "gate_up", "down")
+K_NAMES = ("colsum", "select", "gather_norm", "qkv", "attn", "oproj", "post_norm", "gate_up", "down",
+           "assemble")
 
 EXPORTS = (
     "cc_create", "cc_destroy", "cc_set_stream", "cc_last_error", "cc_select",
     "cc_step_column_scores", "cc_recompute_layer", "cc_step_gather_rmsnorm",
     "cc_step_qkv_rope_scatter", "cc_step_sparse_attention", "cc_step_oproj_residual",
-    "cc_step_mlp", "cc_profile_enable", "cc_profile_read", "cc_calib_copy",
+    "cc_step_mlp", "cc_profile_enable", "cc_profile_read", "cc_calib_copy", "cc_assemble_cache",
 )
 
 
@@ -40,6 +41,10 @@ class ModelDesc(C.Structure):
 class _KV(C.Structure):
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("stride_token", C.c_int64),
                 ("stride_head", C.c_int64), ("N", C.c_int32)]
+
+
+class _Chunk(C.Structure):
+    _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("len", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -86,6 +91,7 @@ def load_library() -> C.CDLL:
     lib.cc_step_oproj_residual.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp]
     lib.cc_step_mlp.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
     lib.cc_calib_copy.argtypes = [vp, vp, vp, i64]
+    lib.cc_assemble_cache.argtypes = [vp, C.POINTER(_Chunk), i32, i32, i64, i64, i32, C.POINTER(_KV)]
     lib.cc_profile_enable.argtypes = [vp, i32]
     lib.cc_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     for name in EXPORTS:
@@ -218,6 +224,18 @@ class Context:
         self._check(self._lib.cc_step_mlp(self._h, y.data_ptr(), M, w_post_norm.data_ptr(),
                                           w_gate.data_ptr(), w_up.data_ptr(), w_down.data_ptr(),
                                           out.data_ptr()))
+
+    # ---- cache assembly ----
+    def assemble_cache(self, chunk_K: Sequence, chunk_V: Sequence, P: int, n_tail: int, dst: KVLayer):
+        """chunk_K[c], chunk_V[c]: cuda bf16 [P + L_c, H_kv, d_h], all with the same strides."""
+        n = len(chunk_K)
+        arr = (_Chunk * n)()
+        st = chunk_K[0].stride()
+        for i, (K, V) in enumerate(zip(chunk_K, chunk_V)):
+            assert K.shape == V.shape and K.stride() == st and V.stride() == st and st[2] == 1
+            arr[i] = _Chunk(K.data_ptr(), V.data_ptr(), K.shape[0] - P)
+        kvs = dst.c_struct()
+        self._check(self._lib.cc_assemble_cache(self._h, arr, n, P, st[0], st[1], n_tail, C.byref(kvs)))
 
     # ---- measurement support ----
     def calib_copy(self, dst, src):

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcacheclip.so")
-SOURCES = ["api.hip", "select.hip", "rows.hip", "gemm.hip", "attention.hip"]
+SOURCES = ["api.hip", "select.hip", "rows.hip", "gemm.hip", "attention.hip", "assemble.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 VALU ops
@@ -19,7 +19,7 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = True, jobs: int = 5) -> str:
+def build_library(verbose: bool = True, jobs: int = 6) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs, procs = [], []
     bdir = os.path.join(PKG, "_build")

@@ -1,6 +1,7 @@
 // C ABI of the library: argument checks, workspace, stream and kernel timing.
 // Every compute step runs in the HIP kernels of this directory.
 #include <math.h>
+#include <algorithm>
 #include <string.h>
 
 #include "cc_internal.h"
@@ -341,6 +342,58 @@ cc_status cc_recompute_layer(cc_ctx* c, const void* hidden, int64_t rows, const 
     st = cc_step_oproj_residual(c, c->o, M, w->w_o, hidden, rows, gather_idx, c->y);
     if (st != CC_OK) return st;
     return cc_step_mlp(c, c->y, M, w->w_post_norm, w->w_gate, w->w_up, w->w_down, out);
+}
+
+cc_status cc_assemble_cache(cc_ctx* c, const cc_chunk_kv* chunks, int32_t n_chunks, int32_t P,
+                            int64_t stride_token, int64_t stride_head, int32_t n_tail,
+                            const cc_kv_layer* dst) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!chunks) return fail(c, CC_ERR_NULL, "chunks must not be NULL");
+    cc_status st = check_kv(c, dst);
+    if (st != CC_OK) return st;
+    if (n_chunks < 1 || P < 0 || n_tail < 0) return fail(c, CC_ERR_SHAPE, "need n_chunks >= 1, P >= 0, n_tail >= 0");
+    if (stride_head < c->m.d_h || stride_head % 8 || stride_token < (int64_t)c->m.d_h * c->m.H_kv ||
+        stride_token % 8)
+        return fail(c, CC_ERR_SHAPE, "chunk strides must be multiples of 8 and cover [H_kv, d_h]");
+    int64_t T = 0;
+    for (int i = 0; i < n_chunks; ++i) {
+        if (!chunks[i].K || !chunks[i].V) return fail(c, CC_ERR_NULL, "chunk K and V must not be NULL");
+        if (chunks[i].len < 1) return fail(c, CC_ERR_SHAPE, "every chunk length must be >= 1");
+        if (!aligned16(chunks[i].K) || !aligned16(chunks[i].V))
+            return fail(c, CC_ERR_SHAPE, "chunk K and V must be 16-byte aligned");
+        T += chunks[i].len;
+    }
+    if ((int64_t)P + T + n_tail > dst->N) return fail(c, CC_ERR_SHAPE, "P + T + n_tail exceeds dst->N");
+    // segments: the prefix (from chunk 0), every chunk's own rows, the zeroed tail
+    std::vector<cc_asm_seg> segs;
+    auto blocks_of = [](int len) { return (len + CC_ASM_ROWS - 1) / CC_ASM_ROWS; };
+    if (P > 0) segs.push_back({(const bf16_t*)chunks[0].K, (const bf16_t*)chunks[0].V, 0, P, 0, 0});
+    int32_t start = 0;
+    for (int i = 0; i < n_chunks; ++i) {
+        segs.push_back({(const bf16_t*)chunks[i].K + (int64_t)P * stride_token,
+                        (const bf16_t*)chunks[i].V + (int64_t)P * stride_token, P + start, chunks[i].len,
+                        start, 0});
+        start += chunks[i].len;
+    }
+    if (n_tail > 0) segs.push_back({nullptr, nullptr, P + start, n_tail, 0, 0});
+    {
+        cc_prof_scope ps(c, CC_K_ASSEMBLE);
+        for (size_t s0 = 0; s0 < segs.size(); s0 += CC_ASM_SEGS) {
+            cc_asm_args a;
+            a.n_seg = (int32_t)std::min<size_t>(CC_ASM_SEGS, segs.size() - s0);
+            int32_t nb = 0;
+            for (int i = 0; i < a.n_seg; ++i) {
+                a.seg[i] = segs[s0 + i];
+                a.seg[i].blk0 = nb;
+                nb += blocks_of(a.seg[i].len);
+            }
+            for (int i = a.n_seg; i < CC_ASM_SEGS; ++i) a.seg[i] = {nullptr, nullptr, 0, 0, 0, nb};
+            a.n_blocks = nb;
+            cc_launch_assemble(a, c->rope, c->m, stride_token, stride_head, *dst, c->stream);
+        }
+    }
+    CC_HIP(c, hipGetLastError());
+    return CC_OK;
 }
 
 cc_status cc_calib_copy(cc_ctx* c, void* dst, const void* src, int64_t bytes) {

@@ -58,6 +58,23 @@ struct cc_prof_scope {
 };
 
 // ---- kernel launchers (each only enqueues on `s`) ----
+// One launch of the assembly kernel covers up to CC_ASM_SEGS source segments.
+#define CC_ASM_SEGS 64
+#define CC_ASM_ROWS 16      // destination rows per wave
+struct cc_asm_seg {
+    const bf16_t* K;        // first source row (NULL: write zeros)
+    const bf16_t* V;
+    int32_t dst;            // first destination row
+    int32_t len;            // rows
+    int32_t delta;          // positions to turn the keys by
+    int32_t blk0;           // first wave-block of this segment within the launch
+};
+struct cc_asm_args {
+    cc_asm_seg seg[CC_ASM_SEGS];
+    int32_t n_seg, n_blocks;
+};
+void cc_launch_assemble(const cc_asm_args& a, const float2* rope, const cc_model_desc& m,
+                        int64_t src_st, int64_t src_sh, const cc_kv_layer& dst, hipStream_t s);
 void cc_launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t s);
 void cc_launch_rope_table(float2* table, int n_pos, int d_h, double base, hipStream_t s);
 void cc_launch_colsum(const float* attn, int Q_a, int T, int64_t ld, float* score, hipStream_t s);
