@@ -101,13 +101,14 @@ def hbm_kernels_c5(dev, reps=20):
         ctx.step_column_scores(A, score)
         ctx.step_gather_rmsnorm(hidden, idx, M, w, xn)
         ctx_a.assemble_cache(cK, cV, wl.P, wl.Q, dst)
+        ctx.calib_copy(dst.V, dst.K)          # plain copy of 135 MB: what a streaming kernel reaches here
     prof = ctx.profile_read()
     prof["assemble"] = ctx_a.profile_read()["assemble"]
     ctx.close()
     ctx_a.close()
     row_bytes = m.H_kv * m.d_h * 2
     work = {"colsum": wl.Q_a * wl.T * 4 + wl.T * 4, "gather_norm": M * m.d * 2 * 2,
-            "assemble": 2 * row_bytes * ((wl.P + wl.T) + wl.N)}
+            "assemble": 2 * row_bytes * ((wl.P + wl.T) + wl.N), "copy": 2 * row_bytes * wl.N}
     out = {"shape": f"C5: A[{wl.Q_a},{wl.T}] fp32; gather {M} of {wl.N} rows, d={m.d}; "
                     f"assemble {len(wl.chunk_lens)} chunk caches into [{wl.N},{m.H_kv},{m.d_h}] K and V"}
     for k, nbytes in work.items():

@@ -201,7 +201,7 @@ cc_status cc_assemble_cache(cc_ctx* ctx, const cc_chunk_kv* chunks, int32_t n_ch
 /* ---- timing of the library's own kernels on its stream ---- */
 enum {
     CC_K_COLSUM = 0, CC_K_SELECT, CC_K_GATHER_NORM, CC_K_QKV, CC_K_ATTN, CC_K_OPROJ,
-    CC_K_POST_NORM, CC_K_GATE_UP, CC_K_DOWN, CC_K_ASSEMBLE, CC_K_COUNT
+    CC_K_POST_NORM, CC_K_GATE_UP, CC_K_DOWN, CC_K_ASSEMBLE, CC_K_COPY, CC_K_COUNT
 };
 /* While enabled, every kernel launch is bracketed by HIP events on the stream. */
 cc_status cc_profile_enable(cc_ctx* ctx, int32_t on);

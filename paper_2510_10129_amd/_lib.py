@@ -16,7 +16,7 @@ CC_OK = 0
 CC_ERR_NULL, CC_ERR_SHAPE, CC_ERR_IDX, CC_ERR_WORKSPACE, CC_ERR_HIP = -1, -2, -3, -4, -5
 FLAG_NO_GROUPING, FLAG_CHECK_IDX = 1, 2
 K_NAMES = ("colsum", "select", "gather_norm", "qkv", "attn", "oproj", "post_norm", "gate_up", "down",
-           "assemble")
+           "assemble", "copy")
 
 EXPORTS = (
     "cc_create", "cc_destroy", "cc_set_stream", "cc_last_error", "cc_select",

@@ -401,7 +401,10 @@ cc_status cc_calib_copy(cc_ctx* c, void* dst, const void* src, int64_t bytes) {
     if (!dst || !src) return fail(c, CC_ERR_NULL, "dst and src must not be NULL");
     if (bytes < 0 || bytes % 16 || !aligned16(dst) || !aligned16(src))
         return fail(c, CC_ERR_SHAPE, "bytes must be a non-negative multiple of 16, pointers 16-byte aligned");
-    cc_launch_copy(dst, src, bytes, c->stream);
+    {
+        cc_prof_scope ps(c, CC_K_COPY);
+        cc_launch_copy(dst, src, bytes, c->stream);
+    }
     CC_HIP(c, hipGetLastError());
     return CC_OK;
 }

@@ -8,7 +8,7 @@
 // (cos, sin) of the segment's position shift are loaded once per wave and kept
 // in registers.  Per key row a lane moves one 16-byte piece of the low half of
 // a head and the matching piece of the high half (the two members of every
-// rotary pair meet in one lane); value rows are 16-byte copies.  Loads of four
+// rotary pair meet in one lane); value rows are 16-byte copies.  Loads of eight
 // rows are issued before their stores.
 #include "cc_internal.h"
 
@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void assemble_kernel(cc_asm_args a, const floa
     constexpr int HALF = D_H / 2;
     constexpr int UPH = HALF / 8;          // (lo, hi) 16-byte pairs per head
     constexpr int CPH = D_H / 8;           // 16-byte chunks per head
-    constexpr int RU = 4;                  // rows in flight
+    constexpr int RU = 8;                  // rows in flight
     const int lane = threadIdx.x & 63;
     const int blk = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
     if (blk >= a.n_blocks) return;
