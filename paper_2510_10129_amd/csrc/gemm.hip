@@ -473,7 +473,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     constexpr int A_I = BM / 16 / NW, B_I = BN / 16 / NW;   // DMA instructions per wave and slice
     constexpr int DPS = A_I + B_I;
     constexpr int SL = (BM + BN) * BKS;
-    static_assert(BM % (16 * NW) == 0 && BN % (32 * NW) == 0, "tile/waves");
+    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0 && BN % 32 == 0, "tile/waves");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
     static_assert(32 * BN * 4 <= SL * 2, "a 32-row fp32 group fits in one slot");
     static_assert(DPS * (NS - 1) < 64, "vmcnt range");
@@ -506,12 +506,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
         r = r < a_rows ? r : a_rows - 1;
         ao[i] = (uint32_t)((r * lda + c * 8) * 2);
     }
+    // B rows: instruction i of this wave covers tile rows (i*NW + wave)*16 .. +15, which lie in
+    // one half of the tile (BN/2 is a multiple of 16); each half has its own base (the gate and
+    // the up matrix of a fused gate/up tile, or simply row BN/2 of the same matrix).
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
     for (int i = 0; i < B_I; ++i) {
-        constexpr int HI = B_I / 2;                       // instructions per half tile
-        const int half = i / HI;
-        int r = ((i % HI) * NW + wave) * 16 + (lane >> 2);   // row within the half
-        const int c = (lane & 3) ^ ((r >> 2) & 3);           // BN/2 is a multiple of 16: same swizzle
+        const int r0 = (i * NW + wave_u) * 16;                // wave-uniform
+        const int half = r0 >= BN / 2 ? 1 : 0;
+        int r = r0 - half * (BN / 2) + (lane >> 2);            // row within the half
+        const int c = (lane & 3) ^ ((r >> 2) & 3);             // same swizzle as for the tile row
         const int left = bsrc.template rows_left<BN>(bn, half);
         r = r < left ? r : left - 1;
         bo[i] = (uint32_t)((r * bsrc.ldb + c * 8) * 2);
@@ -519,7 +523,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     const char* abase = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
     const char* bbase0 = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, 0));
     const char* bbase1 = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, 1));
-    const int wbase = __builtin_amdgcn_readfirstlane(wave) * 16 * BKS;
+    const int wbase = wave_u * 16 * BKS;
     auto scalar_ptr = [](const char* p) -> const char* {   // keeps the base in scalar registers
         const uint64_t u = reinterpret_cast<uint64_t>(p);
         const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
@@ -538,10 +542,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
         }
 #pragma unroll
         for (int i = 0; i < B_I; ++i) {
-            constexpr int HI = B_I / 2;
+            const bool hi_half = (i * NW + wave_u) * 16 >= BN / 2;      // wave-uniform
             asm volatile("" : "+v"(bo[i]));
-            dma16(reinterpret_cast<const bf16_t*>((i < HI ? bb0 : bb1) + bo[i]),
-                  s + BM * BKS + (i / HI) * (BN / 2) * BKS + (i % HI) * NW * 16 * BKS + wbase);
+            dma16(reinterpret_cast<const bf16_t*>((hi_half ? bb1 : bb0) + bo[i]),
+                  s + BM * BKS + i * NW * 16 * BKS + wbase);
         }
     };
 
@@ -637,8 +641,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
 }
 
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
-// workgroup per CU) and 128x128 (4 waves of 64x64, two per CU, measured at 0.6 to
-// 0.9 of the large tile's rate depending on K).  A grid runs as a whole number of "rounds" of workgroups,
+// workgroup per CU), 256x128 (8 waves of 64x64, one per CU, ring loop only) and
+// 128x128 (4 waves of 64x64, two per CU, measured at 0.6 to 0.9 of the large tile's
+// rate depending on K).  A grid runs as a whole number of "rounds" of workgroups,
 // so the shape is chosen per launch to minimise rounds x tile cost.
 template <class BSrc, class Epi>
 void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int ldb, int gm_big,
@@ -657,28 +662,31 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
         const long rounds = (tiles + slots - 1) / slots;
         return (double)rounds * per_cu * bm * bn / eff;
     };
-    const double cb = cost(256, 256, 1, 1.00), cs = cost(128, 128, 2, 0.72);
-    char pick = cb <= cs ? 'b' : 's';
-    if (force && (force[0] == 'b' || force[0] == 's')) pick = force[0];
     // ring loop: whole groups of NS slices, 32-bit lane offsets within a tile's rows
     bool ring = K % (BKS * NS) == 0 && (int64_t)lda * 256 * 2 < (1ll << 31) &&
                 (int64_t)ldb * 256 * 2 < (1ll << 31);
     if (force && force[0] && force[1] == 't') ring = false;
-    const int bm = pick == 'b' ? 256 : 128;
-    const int tiles_m = (M + bm - 1) / bm, tiles_n = (N_tiles_cols + bm - 1) / bm;
-    int GM = pick == 'b' ? gm_big : 2 * gm_big;
+    const double cb = cost(256, 256, 1, 1.00), ch = cost(256, 128, 1, 0.75), cs = cost(128, 128, 2, 0.72);
+    char pick = cb <= cs ? 'b' : 's';
+    if (ring && ch < (pick == 'b' ? cb : cs)) pick = 'h';       // the half-width tile has no staged variant
+    if (force && (force[0] == 'b' || force[0] == 's' || (force[0] == 'h' && ring))) pick = force[0];
+    const int bm = pick == 's' ? 128 : 256, bn = pick == 'b' ? 256 : 128;
+    const int tiles_m = (M + bm - 1) / bm, tiles_n = (N_tiles_cols + bn - 1) / bn;
+    int GM = pick == 's' ? 2 * gm_big : gm_big;
     if (force_gm) GM = atoi(force_gm);
     GM = GM < 1 ? 1 : (GM > tiles_m ? tiles_m : GM);
     const dim3 grid(tiles_m * tiles_n);
-#define CC_LAUNCH(KERN, BM_, WM_, WN_)                                                            \
-    hipLaunchKernelGGL((KERN<BM_, BM_, WM_, WN_, BSrc, Epi>), grid, dim3(WM_ * WN_ * 64), 0, s, A, \
+#define CC_LAUNCH(KERN, BM_, BN_, WM_, WN_)                                                        \
+    hipLaunchKernelGGL((KERN<BM_, BN_, WM_, WN_, BSrc, Epi>), grid, dim3(WM_ * WN_ * 64), 0, s, A, \
                        lda, M, K, tiles_m, tiles_n, GM, bsrc, epi)
     if (pick == 'b') {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 2, 4);
-        else CC_LAUNCH(gemm_nt_kernel, 256, 2, 4);
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4);
+        else CC_LAUNCH(gemm_nt_kernel, 256, 256, 2, 4);
+    } else if (pick == 'h') {
+        CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2);
     } else {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 2, 2);
-        else CC_LAUNCH(gemm_nt_kernel, 128, 2, 2);
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 128, 2, 2);
+        else CC_LAUNCH(gemm_nt_kernel, 128, 128, 2, 2);
     }
 #undef CC_LAUNCH
 }
