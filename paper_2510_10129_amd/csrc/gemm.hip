@@ -225,6 +225,16 @@ __device__ __forceinline__ void dma16(const bf16_t* gsrc, bf16_t* lds_wave_base)
         (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
 }
 
+// Workgroup barrier without the memory fence of __syncthreads() (that fence waits for
+// every outstanding global->LDS load; the ring loop waits only for the slice it needs,
+// with wait_vm_lds0 just before).  The empty asm statements keep the compiler from
+// moving LDS accesses across the barrier.
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // s_waitcnt: at most N vector-memory operations outstanding, no LDS operation.
 template <int N>
 __device__ __forceinline__ void wait_vm_lds0() {
@@ -597,7 +607,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
 #pragma unroll
     for (int j = 0; j < NS; ++j) dma_slice(slot(j), j);
     wait_vm_lds0<DPS * (NS - 1)>();
-    __builtin_amdgcn_s_barrier();
+    wg_barrier();
     load_frags(slot(0), 0, 0);
     int s0 = 0;
     for (; s0 + 2 * NS <= KS; s0 += NS) {
@@ -607,7 +617,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
             mfmas(0);
             pin_interleave();
             wait_vm_lds0<DPS * (NS - 2)>();
-            __builtin_amdgcn_s_barrier();
+            wg_barrier();
             dma_slice(slot(j), s0 + j + NS);
             __builtin_amdgcn_sched_barrier(0);
             load_frags(slot((j + 1) % NS), 0, 0);
@@ -625,7 +635,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
             if (j == 0) wait_vm_lds0<DPS * (NS - 2)>();
             else if (j == 1) wait_vm_lds0<DPS * (NS - 3)>();
             else wait_vm_lds0<0>();
-            __builtin_amdgcn_s_barrier();
+            wg_barrier();
             __builtin_amdgcn_sched_barrier(0);
             load_frags(slot(j + 1), 0, 0);
             mfmas(1);
