@@ -3,10 +3,11 @@
 // the kernel Section 5.6 of the paper describes as flash attention with sparse
 // query indices; the design below is for gfx950.
 //
-// Work split: one workgroup = one kv head x BT consecutive recomputed tokens;
-// the g = H_q/H_kv query heads that share the kv head are packed with the
-// tokens on the 32-wide N side of the MFMA tile (32/g tokens per wave), so a
-// K/V tile read from LDS serves the whole query group.
+// Work split: the (recomputed token, query head of the group) pairs of one kv
+// head form one flat column sequence c = i*g + h (g = H_q/H_kv); a workgroup of
+// eight waves owns 256 consecutive columns, a wave 32 of them on the N side of
+// the MFMA tile, so a K/V tile read from LDS serves the whole query group and
+// no column is padding when g does not divide 32.
 //
 // Each wave computes S^T = K Q^T (keys on the MFMA row side, query rows on the
 // column side).  In the 32x32 accumulator layout a lane then owns ONE query row
@@ -14,6 +15,17 @@
 // reductions plus one exchange with lane^32, the rescale factor is a per-lane
 // scalar, and the probabilities are already laid out as the B operand of
 // O^T = V^T P^T: no shuffle between the two contractions.
+//
+// Two wave groups alternate between the matrix pipe and the vector ALU.  Per
+// 64-key tile a wave issues 32 MFMAs and about as many cycles of exponentials,
+// sums and conversions, one after the other; two independent waves on a SIMD
+// drift into the same phase (both contend for the matrix pipe, then both for
+// the vector ALU) and each pipe idles half of the time.  Here the two waves of a
+// SIMD belong to the same workgroup, one to group A and one to group B, and
+// the workgroup barrier separates phases: while A runs the softmax of tile t, B
+// runs P V of tile t-1 and Q K^T of tile t, and the other way round in the next
+// phase.  Group B also issues all global -> LDS loads, at the start of its
+// softmax phases (a load in the middle of an MFMA sequence stalls that wave).
 //
 // K and V tiles (64 keys) go from the cache straight into LDS with 16-byte
 // global->LDS loads, row-major as they are stored, two stages each.  K
@@ -29,15 +41,50 @@
 // workgroup id modulo H_kv picks the kv head, so the workgroups resident on
 // one XCD walk the same K/V stream through that XCD's L2.
 #include "cc_internal.h"
+#include <type_traits>
 
 namespace {
 
 constexpr int BN_KEYS = 64;
 
-__device__ __forceinline__ void dma16(const bf16_t* gsrc, bf16_t* lds_wave_base) {
+// 16 bytes per lane from global memory straight into LDS.  The LDS address is
+// wave base (M0) + OFF + 16 * lane and OFF is also added to the global address.
+// Rewriting M0 between loads is expensive while MFMAs are in flight (measured:
+// several hundred cycles per rewrite with two MFMA-bound waves on a SIMD), so
+// the loads of one tile and tensor share one base and differ in OFF only.
+template <int OFF>
+__device__ __forceinline__ void dma16(const bf16_t* gsrc_minus_off, bf16_t* lds_wave_base) {
     __builtin_amdgcn_global_load_lds(
-        (const void __attribute__((address_space(1)))*)gsrc,
-        (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
+        (const void __attribute__((address_space(1)))*)gsrc_minus_off,
+        (void __attribute__((address_space(3)))*)lds_wave_base, 16, OFF, 0);
+}
+// LDS reads whose place in the instruction stream is fixed by the source order (the
+// compiler's scheduler, short of registers, would issue every read right before its use).
+// The waits for them are written by hand: LDS operations of a wave return in order, so
+// "at most N outstanding" after N younger reads means this one has arrived.
+template <int IMM>
+__device__ __forceinline__ bf16x4 lds_read_tr_at(uint32_t addr) {
+    bf16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(IMM));
+    return v;
+}
+template <int IMM>
+__device__ __forceinline__ bf16x8 lds_read_b128_at(uint32_t addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(IMM));
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void lds_wait_all_but(bf16x8& x) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
+}
+
+template <int NI, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < NI) {
+        f(std::integral_constant<int, I>{});
+        static_for<NI, I + 1>(f);
+    }
 }
 
 // Transposing LDS read.  Within each group of 16 lanes, lane i receives, as
@@ -47,7 +94,7 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
 }
 
 template <int D_H>
-__global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
+__global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     const bf16_t* __restrict__ q, int M, const int32_t* __restrict__ idx, int H_q, int H_kv,
     const bf16_t* __restrict__ Kc, const bf16_t* __restrict__ Vc, int64_t st, int64_t sh, int N,
     bf16_t* __restrict__ o, int n_row_tiles, float scale_log2) {
@@ -57,35 +104,54 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
     constexpr int RPI = 64 / CPRW;        // rows moved by one global->LDS instruction
     constexpr int NI = BN_KEYS / RPI / 4; // such instructions per wave, tile and tensor
 
-    __shared__ __align__(16) bf16_t Ks0[BN_KEYS * D_H];
-    __shared__ __align__(16) bf16_t Ks1[BN_KEYS * D_H];
-    __shared__ __align__(16) bf16_t Vs0[BN_KEYS * D_H];
-    __shared__ __align__(16) bf16_t Vs1[BN_KEYS * D_H];
+    constexpr int TILE = BN_KEYS * D_H;   // elements of one K or V tile
+    // K tile t lives in stage t % 2 (K loads run two tiles ahead), V tile t in stage
+    // 2 + t % 3 (V loads run three phases ahead)
+    __shared__ __align__(16) bf16_t smem[5 * TILE];
+    auto k_stage = [&](int t) __attribute__((always_inline)) { return smem + (t & 1) * TILE; };
+    auto v_stage = [&](int t) __attribute__((always_inline)) { return smem + (2 + t % 3) * TILE; };
+
+    __shared__ int simd_waves[4], group_waves[2];
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform (scalar) on purpose
+    // Group and slot of this wave.  The two waves that share a SIMD must land in different
+    // groups: the SIMD id comes from the hardware id register (HW_ID bits 5:4), the first
+    // wave to register on a SIMD joins group A (0), the second group B (1).  Should the
+    // eight waves not sit two per SIMD, the split falls back to wave index order (correct,
+    // but the phases of a SIMD's waves then no longer alternate).
+    int grp, widx;
+    {
+        if (tid < 4) simd_waves[tid] = 0;
+        if (tid < 2) group_waves[tid] = 0;
+        __syncthreads();
+        int a = 0, b = 0;
+        if (lane == 0) {
+            const int simd = __builtin_amdgcn_s_getreg(((2 - 1) << 11) | (4 << 6) | 4);
+            a = atomicAdd(&simd_waves[simd & 3], 1) & 1;
+            b = atomicAdd(&group_waves[a], 1);
+        }
+        grp = __builtin_amdgcn_readfirstlane(a);
+        widx = __builtin_amdgcn_readfirstlane(b);
+        __syncthreads();
+        if (group_waves[0] != 4) {
+            const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+            grp = w >> 2;
+            widx = w & 3;
+        }
+    }
+    const int wave = widx;                              // role in the cooperative tile loads
     const int g = H_q / H_kv;
-    const int tw = 32 / g;              // tokens per wave
-    const int BT = 4 * tw;              // tokens per workgroup
     const int kvh = blockIdx.x % H_kv;
     const int rt = n_row_tiles - 1 - blockIdx.x / H_kv;
 
     const int qr = lane & 31, hf = lane >> 5;
-    const int tok_in_wave = qr / g, hg = qr - tok_in_wave * g;
-    const int mi = rt * BT + wave * tw + tok_in_wave;
-    const bool valid = tok_in_wave < tw && mi < M;
+    const int col = rt * 256 + (grp * 4 + widx) * 32 + qr;       // flat (token, head) column
+    const int mi = col / g, hg = col - mi * g;
+    const bool valid = mi < M;
     const int limit = valid ? idx[mi] : -1;
-    const int last_row = min(M - 1, rt * BT + BT - 1);
+    const int last_row = min(M - 1, (rt * 256 + 255) / g);
     const int kmax = idx[last_row];                    // rows are sorted: the block's longest span
     const int n_tiles = kmax / BN_KEYS + 1;
-    // Workgroups with the longest key loops decide when the kernel ends: give their
-    // waves issue priority over the short ones they share a SIMD with.
-    {
-        const int q4 = (4 * n_tiles) / ((N + BN_KEYS - 1) / BN_KEYS + 1);
-        if (q4 >= 3) __builtin_amdgcn_s_setprio(3);
-        else if (q4 == 2) __builtin_amdgcn_s_setprio(2);
-        else if (q4 == 1) __builtin_amdgcn_s_setprio(1);
-    }
 
     // wave-wide largest limit (tiles beyond it are skipped by this wave) and smallest
     // limit of a valid row (tiles that end at or below it need no mask)
@@ -109,57 +175,75 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
         }
     }
 
-    // ---- global -> LDS: instruction i of this wave moves rows (i*4+wave)*RPI .. +RPI-1;
-    //      lane L fills physical chunk L % CPRW of row L / CPRW and fetches the logical
-    //      chunk that the swizzle maps there ----
+    // ---- global -> LDS: instruction i of this wave moves the RPI logical rows
+    //      (i*4 + wave)*RPI ..; lane L fills physical chunk L % CPRW of row L / CPRW and
+    //      fetches the logical chunk that the swizzle maps there.  In LDS the rows of one
+    //      wave's NI instructions are adjacent (physical row rho(r) below), so they are
+    //      reached from one base with immediate offsets of 1 KB ----
     //   K rows: chunk c sits at slot c ^ kswz(row)           (16-byte fragment reads)
     //   V rows: the 64-byte group dt sits at group dt ^ vswz(row)  (transposing 8-byte reads)
+    // The swizzles use row bits that the instruction index does not touch, so one lane
+    // offset per tensor serves every instruction.
     auto kswz = [](int r) { return D_H == 128 ? (r & 15) : ((r >> 1) & 7); };
     auto vswz = [](int r) { return D_H == 128 ? (r & 3) : ((r >> 1) & 1); };
+    constexpr auto rho = [](int r) constexpr { return (((r / RPI) % 4) * NI + r / (4 * RPI)) * RPI + r % RPI; };
+    static_assert((4 * RPI) % 16 == 0 && NI * 1024 <= 4096, "row bits of the swizzle / immediate offset range");
     const bf16_t* kbase = Kc + (int64_t)kvh * sh;
     const bf16_t* vbase = Vc + (int64_t)kvh * sh;
     const int l_row = lane / CPRW, l_p = lane % CPRW;
-    int d_row[NI], k_col[NI], v_col[NI], koff[NI], voff[NI];
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int r = (i * 4 + wave) * RPI + l_row;
-        d_row[i] = r;
-        k_col[i] = (l_p ^ kswz(r)) * 8;
-        v_col[i] = ((((l_p >> 2) ^ vswz(r)) << 2) | (l_p & 3)) * 8;
-        koff[i] = r * (int)st + k_col[i];     // 32-bit lane offsets from a wave-uniform tile base
-        voff[i] = r * (int)st + v_col[i];
-    }
-    auto dma_tile = [&](bf16_t* ks, bf16_t* vs, int j0) {
+    const int r0 = wave * RPI + l_row;                 // logical row of instruction 0
+    const int k_col = (l_p ^ kswz(r0)) * 8;
+    const int v_col = ((((l_p >> 2) ^ vswz(r0)) << 2) | (l_p & 3)) * 8;
+    const int koff = r0 * (int)st + k_col;             // 32-bit lane offsets from a wave-uniform tile base
+    const int voff = r0 * (int)st + v_col;
+    const int64_t istep = (int64_t)(4 * RPI) * st - 512;   // next instruction: 4 RPI rows on, minus its 1 KB immediate
+    const int wave_slot = wave * NI * RPI * D_H;
+    auto dma_k = [&](bf16_t* ks, int j0) __attribute__((always_inline)) {
         const bf16_t* kb = kbase + (int64_t)j0 * st;
-        const bf16_t* vb = vbase + (int64_t)j0 * st;
         if (j0 + BN_KEYS <= N) {
-#pragma unroll
-            for (int i = 0; i < NI; ++i) dma16(kb + koff[i], ks + (i * 4 + wave) * RPI * D_H);
-#pragma unroll
-            for (int i = 0; i < NI; ++i) dma16(vb + voff[i], vs + (i * 4 + wave) * RPI * D_H);
+            static_for<NI>([&](auto i) { dma16<i.value * 1024>(kb + i.value * istep + koff, ks + wave_slot); });
         } else {   // last tile of the cache: rows past N-1 are clamped (they are masked anyway)
             const int rmax = N - 1 - j0;
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                const int r = min(d_row[i], rmax);
-                dma16(kb + (int64_t)r * st + k_col[i], ks + (i * 4 + wave) * RPI * D_H);
-                dma16(vb + (int64_t)r * st + v_col[i], vs + (i * 4 + wave) * RPI * D_H);
-            }
+            static_for<NI>([&](auto i) {
+                const int64_t r = min(r0 + i.value * 4 * RPI, rmax);
+                dma16<i.value * 1024>(kb + r * st + k_col - i.value * 512, ks + wave_slot);
+            });
         }
-        __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the tile's math
+    };
+    auto dma_v = [&](bf16_t* vs, int j0) __attribute__((always_inline)) {
+        const bf16_t* vb = vbase + (int64_t)j0 * st;
+        if (j0 + BN_KEYS <= N) {
+            static_for<NI>([&](auto i) { dma16<i.value * 1024>(vb + i.value * istep + voff, vs + wave_slot); });
+        } else {
+            const int rmax = N - 1 - j0;
+            static_for<NI>([&](auto i) {
+                const int64_t r = min(r0 + i.value * 4 * RPI, rmax);
+                dma16<i.value * 1024>(vb + r * st + v_col - i.value * 512, vs + wave_slot);
+            });
+        }
     };
 
-    // ---- fragment addresses ----
-    // K: row kt*32 + qr, logical chunk 2 ks + hf
-    const int k_frag_row = qr * D_H;
+    // ---- fragment addresses: LDS byte addresses in the stage this wave reads next (they
+    //      move on after every matrix phase); key block and half are immediate offsets ----
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)smem;
+    // K: logical row kt*32 + qr (physical rho(qr) + 8 kt), logical chunk 2 ks + hf
     const int k_sw = kswz(qr);
+    uint32_t kaddr[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        kaddr[ks] = smem_base + 2 * (rho(qr) * D_H + (((ks * 2 + hf) ^ k_sw) << 3));
     // V^T through the transposing read: lane s of a 16-lane group addresses key
     // (4 hf + s/4) and the 4 d's starting at 16*(group%2) + 4*(s%4); the lane then
-    // holds 4 consecutive keys of column d = 32 dt + lane%32.
+    // holds 4 consecutive keys of column d = 32 dt + lane%32.  Key 16 ss + 8 e + v_key sits
+    // in physical row rho(16 ss + 8 e) + rho(v_key) (the two parts use different row bits).
     const int s16 = lane & 15, dsub = (lane >> 4) & 1;
     const int v_key = 4 * hf + (s16 >> 2);
     const int v_sw = vswz(v_key);
-    const int v_lane = v_key * D_H + (2 * dsub + ((s16 & 3) >> 1)) * 8 + (s16 & 1) * 4;
+    const int v_lane = (2 * dsub + ((s16 & 3) >> 1)) * 8 + (s16 & 1) * 4;
+    uint32_t vaddr[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+        vaddr[dt] = smem_base + 2 * (2 * TILE + rho(v_key) * D_H + v_lane + ((dt ^ v_sw) << 5));
 
     f32x16 acc_o[DT];
 #pragma unroll
@@ -167,24 +251,13 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_o[dt][v] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
+    f32x16 s[2];       // S^T tile: 64 keys x 32 query rows
+    bf16x8 pf[4];      // its probabilities as B operand of the second contraction
 
-    auto tile_math = [&](const bf16_t* ks_, const bf16_t* vs_, int j0) {
-        // ---- S^T tile: 64 keys x 32 query rows ----
-        f32x16 s[2];
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[kt][v] = 0.0f;
-        // the two 32-key halves are independent accumulation chains: alternate them
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int kc = (ks * 2 + hf) ^ k_sw;
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks_ + kt * 32 * D_H + k_frag_row + (kc << 3));
-                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
-            }
-        }
+    // `loads` issues NL global -> LDS loads; they are spread over the exponentials (a burst
+    // of loads fills the CU's vector-memory queue and the issuing wave stalls on it)
+    auto softmax = [&](int j0, auto nl_c, bool spread, auto&& loads) __attribute__((always_inline)) {
+        constexpr int NL = decltype(nl_c)::value;
         // ---- causal mask (only in tiles that reach past the wave's first row),
         //      online softmax in base 2 with the 1/sqrt(d_h) scale folded into the exponent ----
         if (j0 + BN_KEYS - 1 > wave_min) {
@@ -219,48 +292,163 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(
         }
         const float m_use = m_run == -INFINITY ? 0.0f : m_run;
         float psum = 0.0f;
-        bf16x8 pf[4];
+        // four scores at a time: exponentials, their sum and their bf16 pair conversions are
+        // finished before the next four start (keeps only four probabilities live)
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float p = __builtin_amdgcn_exp2f(fmaf(s[kt][v], scale_log2, -m_use));
-                psum += p;
-                pf[kt * 2 + (v >> 3)][v & 7] = (bf16_t)p;
+        for (int c = 0; c < 8; ++c) {
+            const int kt = c >> 2, v0 = (c & 3) * 4;
+            if constexpr (NL > 0) {
+                if (c % (8 / NL) == 0 && spread) loads(c / (8 / NL));
             }
-        l_run += psum;
-        // ---- O^T += V^T P^T: slots 0..3 <- keys 16ss+4hf.., slots 4..7 <- keys 16ss+8+4hf.. ----
+            float pv[4];
 #pragma unroll
-        for (int ss = 0; ss < 4; ++ss) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {      // DT independent accumulation chains
-                const bf16_t* vcol = vs_ + v_lane + ((dt ^ v_sw) << 5);
-                bf16x4 a0 = lds_read_tr(vcol + (16 * ss) * D_H);
-                bf16x4 a1 = lds_read_tr(vcol + (16 * ss + 8) * D_H);
-                bf16x8 vf;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    vf[u] = a0[u];
-                    vf[4 + u] = a1[u];
-                }
-                acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ss], acc_o[dt], 0, 0, 0);
-            }
+            for (int u = 0; u < 4; ++u) pv[u] = __builtin_amdgcn_exp2f(fmaf(s[kt][v0 + u], scale_log2, -m_use));
+            psum += (pv[0] + pv[1]) + (pv[2] + pv[3]);
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+            bf16x2 lo = __builtin_convertvector(f32x2{pv[0], pv[1]}, bf16x2);
+            bf16x2 hi = __builtin_convertvector(f32x2{pv[2], pv[3]}, bf16x2);
+            asm volatile("" : "+v"(lo), "+v"(hi));   // converted here, not gathered at the end
+            bf16x8& dst = pf[kt * 2 + (v0 >> 3)];
+            dst[(v0 & 7) + 0] = lo[0];
+            dst[(v0 & 7) + 1] = lo[1];
+            dst[(v0 & 7) + 2] = hi[0];
+            dst[(v0 & 7) + 3] = hi[1];
         }
+        l_run += psum;
+    };
+    // End of a phase: at most `pending` of this wave's global -> LDS loads may still be in
+    // flight (0 or NI: the ones issued in this phase), then the workgroup barrier.  The tile
+    // reads are written by hand, so no compiler-made wait is needed around the barrier.
+    auto phase_end = [&](bool pending) __attribute__((always_inline)) {
+        if (pending) __builtin_amdgcn_s_waitcnt((NI & 0xF) | ((NI >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+        else __builtin_amdgcn_s_waitcnt((0x7 << 4) | (0xF << 8));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // Matrix phase of one wave: O^T += V^T P^T for the V tile at vaddr (with_pv), then
+    // S^T = K Q^T for the K tile at kaddr.  The other wave of the SIMD is in
+    // its softmax, so this wave alone has to keep the matrix pipe fed: the LDS reads of MFMA
+    // j + PD are issued before MFMA j.  P V: MFMA j = (ss, dt) = (j / DT, j % DT), DT
+    // independent accumulation chains; A slots 0..3 <- keys 16ss+4hf.., 4..7 <- keys
+    // 16ss+8+4hf..  Scores: MFMA n = (ks, kt) = (n / 2, n % 2), two chains.
+    constexpr int PD = 4;
+    auto matrix_phase = [&](auto with_pv) __attribute__((always_inline)) {
+        constexpr int NPV = decltype(with_pv)::value ? 4 * DT : 0, NQK = 2 * KS, NALL = NPV + NQK;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        bf16x8 opnd[NALL];
+        auto issue = [&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            if constexpr (j < NPV) {
+                constexpr int ss = j / DT, dt = j % DT;
+                constexpr int at = 2 * rho(16 * ss) * D_H;
+                constexpr int at8 = 2 * rho(16 * ss + 8) * D_H;
+                const bf16x4 a0 = lds_read_tr_at<at>(vaddr[dt]);
+                const bf16x4 a1 = lds_read_tr_at<at8>(vaddr[dt]);
+                opnd[j] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+            } else if constexpr (j < NALL) {
+                constexpr int n = j - NPV, ks = n / 2, kt = n % 2;
+                opnd[j] = lds_read_b128_at<2 * kt * 8 * D_H>(kaddr[ks]);
+            }
+        };
+        static_for<PD>(issue);
+        static_for<NALL>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            issue(std::integral_constant<int, j + PD>{});
+            constexpr int last = j + PD < NALL ? j + PD : NALL - 1;
+            constexpr int npv_after = (last < NPV ? last : NPV - 1) - j > 0 ? (last < NPV ? last : NPV - 1) - j : 0;
+            constexpr int younger = (last - j) + npv_after;       // a P V operand is two reads
+            lds_wait_all_but<younger>(opnd[j]);
+            if constexpr (j < NPV) {
+                constexpr int ss = j / DT, dt = j % DT;
+                acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[j], pf[ss], acc_o[dt], 0, 0, 0);
+            } else {
+                constexpr int n = j - NPV, ks = n / 2, kt = n % 2;
+                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[j], qf[ks], ks == 0 ? zero : s[kt], 0, 0, 0);
+            }
+        });
     };
 
-    // ---- key loop: the next tile streams into the idle stage while this one is used;
-    //      the barrier waits for the loads (vmcnt) and for every wave to leave the stage ----
-    dma_tile(Ks0, Vs0, 0);
-    __syncthreads();
-    for (int t = 0; t < n_tiles; t += 2) {
-        const int j0 = t * BN_KEYS;
-        if (t + 1 < n_tiles) dma_tile(Ks1, Vs1, j0 + BN_KEYS);
-        if (j0 <= wave_limit) tile_math(Ks0, Vs0, j0);
-        __syncthreads();
-        if (t + 1 < n_tiles) {
-            if (t + 2 < n_tiles) dma_tile(Ks0, Vs0, j0 + 2 * BN_KEYS);
-            if (j0 + BN_KEYS <= wave_limit) tile_math(Ks1, Vs1, j0 + BN_KEYS);
-            __syncthreads();
+    // ---- phases.  P0: A scores(0).  P(2t+1): A softmax(t), loads V(t+1) | B values(t-1),
+    //      scores(t).  P(2t+2): A values(t), scores(t+1) | B softmax(t), loads K(t+2).
+    //      V(t+1) goes to the stage V(t-2) left at the end of P(2t-1) and is first read in
+    //      P(2t+4): group A waits for it at the end of P(2t+3), with V(t+2) still in flight.
+    //      K(t+2) goes to the stage K(t) left at the end of P(2t+1) and is first read in
+    //      P(2t+4): group B waits for it at the end of P(2t+3).  Every wave passes 2 n_tiles + 3
+    //      barriers; tiles past a wave's own last key only cost it the barriers and its loads.
+    //      The scores of tile my_tiles (computed from whatever its stage holds) are never used.
+    const int my_tiles = wave_limit < 0 ? 0 : wave_limit / BN_KEYS + 1;
+    using yes = std::integral_constant<int, 1>;
+    using no = std::integral_constant<int, 0>;
+    int k_next = 1, v_cur = 0;        // K stage the address registers move to next / V stage they are at
+    auto advance = [&](bool also_v) __attribute__((always_inline)) {
+        const int kd = k_next ? 2 * TILE : -2 * TILE;
+        k_next ^= 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kaddr[ks] += kd;
+        if (also_v) {
+            const int vd = v_cur == 2 ? -4 * TILE : 2 * TILE;
+            v_cur = v_cur == 2 ? 0 : v_cur + 1;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) vaddr[dt] += vd;
+        }
+    };
+    // softmax of tile t and the NI loads of `tile` (a K or V tile, by `is_k`) into `dst`
+    auto softmax_and_load = [&](int t, bool have_load, bool is_k, int tile, bf16_t* dst) __attribute__((always_inline)) {
+        // a whole tile is issued between the exponentials, anything else up front
+        const bool spread = have_load && t < my_tiles && (tile + 1) * BN_KEYS <= N;
+        if (have_load && !spread) {
+            if (is_k) dma_k(dst, tile * BN_KEYS);
+            else dma_v(dst, tile * BN_KEYS);
+        }
+        if (t < my_tiles) {
+            const bf16_t* gb = (is_k ? kbase + koff : vbase + voff) + (int64_t)tile * BN_KEYS * st;
+            softmax(t * BN_KEYS, std::integral_constant<int, NI>{}, spread, [&](int e) __attribute__((always_inline)) {
+                static_for<NI>([&](auto i) {
+                    if (e == i.value) dma16<i.value * 1024>(gb + i.value * istep, dst + wave_slot);
+                });
+            });
+        }
+    };
+    if (grp == 0) {
+        dma_v(v_stage(0), 0);
+        phase_end(false);                                  // K(0), K(1), V(0) are in place
+        if (my_tiles > 0) {                                // P0
+            matrix_phase(no{});
+            advance(false);
+        }
+        phase_end(false);
+        for (int t = 0; t < n_tiles; ++t) {
+            const bool ld = t + 1 < n_tiles;
+            softmax_and_load(t, ld, false, t + 1, v_stage(t + 1));
+            phase_end(ld);                                 // V(t) has landed
+            if (t < my_tiles) {
+                matrix_phase(yes{});
+                advance(true);
+            }
+            phase_end(ld);
+        }
+        phase_end(false);
+    } else {
+        dma_k(k_stage(0), 0);
+        if (n_tiles > 1) dma_k(k_stage(1), BN_KEYS);
+        phase_end(false);                                  // K(0), K(1), V(0) are in place
+        phase_end(false);                                  // P0
+        if (my_tiles > 0) {                                // P1
+            matrix_phase(no{});
+            advance(false);
+        }
+        phase_end(false);
+        for (int t = 0; t < n_tiles; ++t) {
+            const bool ld = t + 2 < n_tiles;
+            softmax_and_load(t, ld, true, t + 2, k_stage(t));
+            phase_end(ld);
+            if (t < my_tiles) {
+                matrix_phase(yes{});
+                advance(true);
+            }
+            phase_end(false);                              // K(t+2) has landed
         }
     }
 
@@ -287,10 +475,9 @@ void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_mo
                          const cc_kv_layer& kv, bf16_t* o, hipStream_t s) {
     if (M <= 0) return;
     const int g = m.H_q / m.H_kv;
-    const int BT = 4 * (32 / g);
-    const int n_row_tiles = (M + BT - 1) / BT;
+    const int n_row_tiles = (int)(((int64_t)M * g + 255) / 256);   // 256 (token, head) columns each
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)m.d_h);
-    dim3 grid(n_row_tiles * m.H_kv), block(256);
+    dim3 grid(n_row_tiles * m.H_kv), block(512);
     if (m.d_h == 128)
         hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, block, 0, s, q, M, idx, m.H_q, m.H_kv,
                            (const bf16_t*)kv.K, (const bf16_t*)kv.V, kv.stride_token, kv.stride_head,
