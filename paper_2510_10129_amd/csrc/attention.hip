@@ -105,11 +105,10 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     constexpr int NI = BN_KEYS / RPI / 4; // such instructions per wave, tile and tensor
 
     constexpr int TILE = BN_KEYS * D_H;   // elements of one K or V tile
-    // K tile t lives in stage t % 2 (K loads run two tiles ahead), V tile t in stage
-    // 2 + t % 3 (V loads run three phases ahead)
-    __shared__ __align__(16) bf16_t smem[5 * TILE];
-    auto k_stage = [&](int t) __attribute__((always_inline)) { return smem + (t & 1) * TILE; };
-    auto v_stage = [&](int t) __attribute__((always_inline)) { return smem + (2 + t % 3) * TILE; };
+    // three stages per tensor: K tile t lives in stage t % 3, V tile t in stage 3 + t % 3
+    __shared__ __align__(16) bf16_t smem[6 * TILE];
+    auto k_stage = [&](int t) __attribute__((always_inline)) { return smem + (t % 3) * TILE; };
+    auto v_stage = [&](int t) __attribute__((always_inline)) { return smem + (3 + t % 3) * TILE; };
 
     __shared__ int simd_waves[4], group_waves[2];
 
@@ -243,7 +242,7 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     uint32_t vaddr[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
-        vaddr[dt] = smem_base + 2 * (2 * TILE + rho(v_key) * D_H + v_lane + ((dt ^ v_sw) << 5));
+        vaddr[dt] = smem_base + 2 * (3 * TILE + rho(v_key) * D_H + v_lane + ((dt ^ v_sw) << 5));
 
     f32x16 acc_o[DT];
 #pragma unroll
@@ -254,10 +253,7 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     f32x16 s[2];       // S^T tile: 64 keys x 32 query rows
     bf16x8 pf[4];      // its probabilities as B operand of the second contraction
 
-    // `loads` issues NL global -> LDS loads; they are spread over the exponentials (a burst
-    // of loads fills the CU's vector-memory queue and the issuing wave stalls on it)
-    auto softmax = [&](int j0, auto nl_c, bool spread, auto&& loads) __attribute__((always_inline)) {
-        constexpr int NL = decltype(nl_c)::value;
+    auto softmax = [&](int j0) __attribute__((always_inline)) {
         // ---- causal mask (only in tiles that reach past the wave's first row),
         //      online softmax in base 2 with the 1/sqrt(d_h) scale folded into the exponent ----
         if (j0 + BN_KEYS - 1 > wave_min) {
@@ -297,9 +293,6 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             const int kt = c >> 2, v0 = (c & 3) * 4;
-            if constexpr (NL > 0) {
-                if (c % (8 / NL) == 0 && spread) loads(c / (8 / NL));
-            }
             float pv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) pv[u] = __builtin_amdgcn_exp2f(fmaf(s[kt][v0 + u], scale_log2, -m_use));
@@ -317,8 +310,8 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
         }
         l_run += psum;
     };
-    // End of a phase: at most `pending` of this wave's global -> LDS loads may still be in
-    // flight (0 or NI: the ones issued in this phase), then the workgroup barrier.  The tile
+    // End of a phase: all of this wave's global -> LDS loads but the newest tile's
+    // (`pending`) have landed, then the workgroup barrier.  The tile
     // reads are written by hand, so no compiler-made wait is needed around the barrier.
     auto phase_end = [&](bool pending) __attribute__((always_inline)) {
         if (pending) __builtin_amdgcn_s_waitcnt((NI & 0xF) | ((NI >> 4) << 14) | (0x7 << 4) | (0xF << 8));
@@ -333,11 +326,17 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     // j + PD are issued before MFMA j.  P V: MFMA j = (ss, dt) = (j / DT, j % DT), DT
     // independent accumulation chains; A slots 0..3 <- keys 16ss+4hf.., 4..7 <- keys
     // 16ss+8+4hf..  Scores: MFMA n = (ks, kt) = (n / 2, n % 2), two chains.
-    constexpr int PD = 4;
+#ifndef CC_ATTN_PD
+#define CC_ATTN_PD 4
+#endif
+    constexpr int PD = CC_ATTN_PD;
     auto matrix_phase = [&](auto with_pv) __attribute__((always_inline)) {
         constexpr int NPV = decltype(with_pv)::value ? 4 * DT : 0, NQK = 2 * KS, NALL = NPV + NQK;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         bf16x8 opnd[NALL];
+#ifdef CC_ATTN_PRIO
+        __builtin_amdgcn_s_setprio(3);
+#endif
         auto issue = [&](auto jc) __attribute__((always_inline)) {
             constexpr int j = decltype(jc)::value;
             if constexpr (j < NPV) {
@@ -368,87 +367,80 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
                 s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[j], qf[ks], ks == 0 ? zero : s[kt], 0, 0, 0);
             }
         });
+#ifdef CC_ATTN_PRIO
+        __builtin_amdgcn_s_setprio(0);
+#endif
     };
 
-    // ---- phases.  P0: A scores(0).  P(2t+1): A softmax(t), loads V(t+1) | B values(t-1),
-    //      scores(t).  P(2t+2): A values(t), scores(t+1) | B softmax(t), loads K(t+2).
-    //      V(t+1) goes to the stage V(t-2) left at the end of P(2t-1) and is first read in
-    //      P(2t+4): group A waits for it at the end of P(2t+3), with V(t+2) still in flight.
-    //      K(t+2) goes to the stage K(t) left at the end of P(2t+1) and is first read in
-    //      P(2t+4): group B waits for it at the end of P(2t+3).  Every wave passes 2 n_tiles + 3
-    //      barriers; tiles past a wave's own last key only cost it the barriers and its loads.
-    //      The scores of tile my_tiles (computed from whatever its stage holds) are never used.
+    // ---- phases.  P0: A scores(0).  P(2t+1): A softmax(t) | B values(t-1), scores(t).
+    //      P(2t+2): A values(t), scores(t+1) | B softmax(t).  A wave issues its loads at the
+    //      end of its matrix phase, while its SIMD partner is in the softmax: next to a partner
+    //      that keeps the matrix pipe busy a vector-memory instruction takes several times as
+    //      long to issue.  Group A loads V(t+2) at the end of P(2t+2) into the stage V(t-1)
+    //      left at the end of P(2t+1); it is first read in P(2t+6) and group A waits for it at
+    //      the end of P(2t+5), with V(t+3) still in flight.  Group B loads K(t+3) at the end of
+    //      P(2t+3) into the stage K(t) left at the end of P(2t+1); first read in P(2t+6), group
+    //      B waits for it at the end of P(2t+5), after issuing K(t+4).  Every wave passes
+    //      2 n_tiles + 3 barriers; tiles past a wave's own last key only cost it the barriers
+    //      and its loads.  The scores of tile my_tiles (computed from whatever its stage holds)
+    //      are never used.
     const int my_tiles = wave_limit < 0 ? 0 : wave_limit / BN_KEYS + 1;
     using yes = std::integral_constant<int, 1>;
     using no = std::integral_constant<int, 0>;
-    int k_next = 1, v_cur = 0;        // K stage the address registers move to next / V stage they are at
+    int k_at = 0, v_at = 0;           // stages the address registers point at
     auto advance = [&](bool also_v) __attribute__((always_inline)) {
-        const int kd = k_next ? 2 * TILE : -2 * TILE;
-        k_next ^= 1;
+        const int kd = k_at == 2 ? -4 * TILE : 2 * TILE;
+        k_at = k_at == 2 ? 0 : k_at + 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) kaddr[ks] += kd;
         if (also_v) {
-            const int vd = v_cur == 2 ? -4 * TILE : 2 * TILE;
-            v_cur = v_cur == 2 ? 0 : v_cur + 1;
+            const int vd = v_at == 2 ? -4 * TILE : 2 * TILE;
+            v_at = v_at == 2 ? 0 : v_at + 1;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) vaddr[dt] += vd;
         }
     };
-    // softmax of tile t and the NI loads of `tile` (a K or V tile, by `is_k`) into `dst`
-    auto softmax_and_load = [&](int t, bool have_load, bool is_k, int tile, bf16_t* dst) __attribute__((always_inline)) {
-        // a whole tile is issued between the exponentials, anything else up front
-        const bool spread = have_load && t < my_tiles && (tile + 1) * BN_KEYS <= N;
-        if (have_load && !spread) {
-            if (is_k) dma_k(dst, tile * BN_KEYS);
-            else dma_v(dst, tile * BN_KEYS);
-        }
-        if (t < my_tiles) {
-            const bf16_t* gb = (is_k ? kbase + koff : vbase + voff) + (int64_t)tile * BN_KEYS * st;
-            softmax(t * BN_KEYS, std::integral_constant<int, NI>{}, spread, [&](int e) __attribute__((always_inline)) {
-                static_for<NI>([&](auto i) {
-                    if (e == i.value) dma16<i.value * 1024>(gb + i.value * istep, dst + wave_slot);
-                });
-            });
-        }
-    };
     if (grp == 0) {
         dma_v(v_stage(0), 0);
-        phase_end(false);                                  // K(0), K(1), V(0) are in place
+        if (n_tiles > 1) dma_v(v_stage(1), BN_KEYS);
+        phase_end(n_tiles > 1);                            // K(0), V(0) are in place
         if (my_tiles > 0) {                                // P0
             matrix_phase(no{});
             advance(false);
         }
-        phase_end(false);
+        phase_end(n_tiles > 1);
         for (int t = 0; t < n_tiles; ++t) {
-            const bool ld = t + 1 < n_tiles;
-            softmax_and_load(t, ld, false, t + 1, v_stage(t + 1));
-            phase_end(ld);                                 // V(t) has landed
+            if (t < my_tiles) softmax(t * BN_KEYS);
+            phase_end(t + 1 < n_tiles);                    // V(t) has landed
             if (t < my_tiles) {
                 matrix_phase(yes{});
                 advance(true);
             }
-            phase_end(ld);
+            if (t + 2 < n_tiles) dma_v(v_stage(t + 2), (t + 2) * BN_KEYS);
+            phase_end(true);
         }
         phase_end(false);
     } else {
         dma_k(k_stage(0), 0);
         if (n_tiles > 1) dma_k(k_stage(1), BN_KEYS);
-        phase_end(false);                                  // K(0), K(1), V(0) are in place
-        phase_end(false);                                  // P0
+        if (n_tiles > 2) dma_k(k_stage(2), 2 * BN_KEYS);
+        if (n_tiles > 2) __builtin_amdgcn_s_waitcnt(((2 * NI) & 0xF) | (((2 * NI) >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+        phase_end(n_tiles > 1);                            // K(0), V(0) are in place
+        phase_end(true);                                   // P0
         if (my_tiles > 0) {                                // P1
             matrix_phase(no{});
             advance(false);
         }
-        phase_end(false);
+        phase_end(n_tiles > 2);                            // K(1) has landed
         for (int t = 0; t < n_tiles; ++t) {
-            const bool ld = t + 2 < n_tiles;
-            softmax_and_load(t, ld, true, t + 2, k_stage(t));
-            phase_end(ld);
+            if (t < my_tiles) softmax(t * BN_KEYS);
+            phase_end(true);
             if (t < my_tiles) {
                 matrix_phase(yes{});
                 advance(true);
             }
-            phase_end(false);                              // K(t+2) has landed
+            if (t + 3 < n_tiles) dma_k(k_stage(t), (t + 3) * BN_KEYS);
+            phase_end(t + 3 < n_tiles);                    // K(t+2) has landed
         }
     }
 
