@@ -21,6 +21,7 @@
 #include <stdlib.h>
 
 #include "cc_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -223,6 +224,22 @@ __device__ __forceinline__ void dma16(const bf16_t* gsrc, bf16_t* lds_wave_base)
     __builtin_amdgcn_global_load_lds(
         (const void __attribute__((address_space(1)))*)gsrc,
         (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
+}
+
+// The same with an immediate offset, added to both the LDS and the global address: loads
+// that share a wave base need no rewrite of M0 between them.
+template <int OFF>
+__device__ __forceinline__ void dma16_at(const char* gsrc_minus_off, bf16_t* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds(
+        (const void __attribute__((address_space(1)))*)gsrc_minus_off,
+        (void __attribute__((address_space(3)))*)lds_wave_base, 16, OFF, 0);
+}
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void unrolled(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        unrolled<N, I + 1>(f);
+    }
 }
 
 // Workgroup barrier without the memory fence of __syncthreads() (that fence waits for
@@ -505,35 +522,37 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     // One DMA instruction moves 16 slice rows (16 x 64 B).  Lane L fills physical
     // chunk slot L%4 of row L/4 and fetches the logical chunk slot ^ ((row>>2)&3):
     // a 16-byte fragment read of 16 consecutive rows then touches every bank once.
+    // Wave w loads A rows w*16*A_I .. and B rows w*16*B_I .. of the tile, and a slot holds
+    // them wave by wave ([wave][A rows | B rows], DPS KB each): the DPS loads of a wave and
+    // slice share one LDS base and differ in their immediate offset only.
     // Global addresses are a wave-uniform base (advanced along K in scalar
     // registers) plus a loop-invariant 32-bit lane offset.
     uint32_t ao[A_I], bo[B_I];
     const int a_rows = M - m0;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
     for (int i = 0; i < A_I; ++i) {
-        int r = (i * NW + wave) * 16 + (lane >> 2);
+        int r = (wave_u * A_I + i) * 16 + (lane >> 2);
         const int c = (lane & 3) ^ ((r >> 2) & 3);
         r = r < a_rows ? r : a_rows - 1;
         ao[i] = (uint32_t)((r * lda + c * 8) * 2);
     }
-    // B rows: instruction i of this wave covers tile rows (i*NW + wave)*16 .. +15, which lie in
-    // one half of the tile (BN/2 is a multiple of 16); each half has its own base (the gate and
-    // the up matrix of a fused gate/up tile, or simply row BN/2 of the same matrix).
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    // B rows: the rows of one wave lie in one half of the tile (BN/2 is a multiple of
+    // 16*B_I); each half has its own base (the gate and the up matrix of a fused gate/up tile,
+    // or simply row BN/2 of the same matrix).
+    static_assert((BN / 2) % (16 * B_I) == 0, "a wave's B rows stay in one half");
+    const bool hi_half = wave_u * B_I * 16 >= BN / 2;          // wave-uniform
 #pragma unroll
     for (int i = 0; i < B_I; ++i) {
-        const int r0 = (i * NW + wave_u) * 16;                // wave-uniform
-        const int half = r0 >= BN / 2 ? 1 : 0;
-        int r = r0 - half * (BN / 2) + (lane >> 2);            // row within the half
+        int r = (wave_u * B_I + i) * 16 - (hi_half ? BN / 2 : 0) + (lane >> 2);   // row within the half
         const int c = (lane & 3) ^ ((r >> 2) & 3);             // same swizzle as for the tile row
-        const int left = bsrc.template rows_left<BN>(bn, half);
+        const int left = bsrc.template rows_left<BN>(bn, hi_half ? 1 : 0);
         r = r < left ? r : left - 1;
         bo[i] = (uint32_t)((r * bsrc.ldb + c * 8) * 2);
     }
     const char* abase = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
-    const char* bbase0 = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, 0));
-    const char* bbase1 = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, 1));
-    const int wbase = wave_u * 16 * BKS;
+    const char* bbase = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, hi_half ? 1 : 0));
+    const int wbase = wave_u * DPS * 16 * BKS;
     auto scalar_ptr = [](const char* p) -> const char* {   // keeps the base in scalar registers
         const uint64_t u = reinterpret_cast<uint64_t>(p);
         const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
@@ -542,21 +561,22 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     };
     auto dma_slice = [&](bf16_t* s, int sidx) {
         const int64_t kb = (int64_t)sidx * (BKS * 2);
-        const char* ab = scalar_ptr(abase + kb);
-        const char* bb0 = scalar_ptr(bbase0 + kb);
-        const char* bb1 = scalar_ptr(bbase1 + kb);
-#pragma unroll
-        for (int i = 0; i < A_I; ++i) {
-            asm volatile("" : "+v"(ao[i]));   // keeps the offset a 32-bit register operand of the load
-            dma16(reinterpret_cast<const bf16_t*>(ab + ao[i]), s + i * NW * 16 * BKS + wbase);
-        }
-#pragma unroll
-        for (int i = 0; i < B_I; ++i) {
-            const bool hi_half = (i * NW + wave_u) * 16 >= BN / 2;      // wave-uniform
-            asm volatile("" : "+v"(bo[i]));
-            dma16(reinterpret_cast<const bf16_t*>((hi_half ? bb1 : bb0) + bo[i]),
-                  s + BM * BKS + i * NW * 16 * BKS + wbase);
-        }
+        unrolled<A_I>([&](auto i) {
+            const char* ab = scalar_ptr(abase + kb - i.value * 1024);   // the immediate adds it back
+            asm volatile("" : "+v"(ao[i.value]));   // keeps the offset a 32-bit register operand of the load
+            dma16_at<i.value * 1024>(ab + ao[i.value], s + wbase);
+        });
+        unrolled<B_I>([&](auto i) {
+            const char* bb = scalar_ptr(bbase + kb - (A_I + i.value) * 1024);
+            asm volatile("" : "+v"(bo[i.value]));
+            dma16_at<(A_I + i.value) * 1024>(bb + bo[i.value], s + wbase);
+        });
+    };
+    // element offset in a slot of tile row r of A (is_b = 0) or B (is_b = 1)
+    auto row_at = [](int r, int is_b) {
+        constexpr int per_a = 16 * A_I, per_b = 16 * B_I;
+        return is_b ? ((r / per_b) * DPS * 16 + A_I * 16 + r % per_b) * BKS
+                    : ((r / per_a) * DPS * 16 + r % per_a) * BKS;
     };
 
     f32x16 acc[TM][TN];
@@ -574,10 +594,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
         const int sl = ((ks * 2 + fk) ^ fsw) << 3;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            af[fb][i] = *reinterpret_cast<const bf16x8*>(s + (wm0 + i * 32 + frow) * BKS + sl);
+            af[fb][i] = *reinterpret_cast<const bf16x8*>(s + row_at(wm0 + i * 32 + frow, 0) + sl);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            bfr[fb][j] = *reinterpret_cast<const bf16x8*>(s + BM * BKS + (wn0 + j * 32 + frow) * BKS + sl);
+            bfr[fb][j] = *reinterpret_cast<const bf16x8*>(s + row_at(wn0 + j * 32 + frow, 1) + sl);
     };
     auto mfmas = [&](int fb) {
 #pragma unroll
