@@ -215,6 +215,57 @@ def test_stage_attention_peaked_random():
         ctx.close()
 
 
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 127, 128, 129, 192, 193, 257, 320])
+def test_stage_attention_key_tile_boundaries(N):
+    """Cache lengths around the 64-key tile and the three-stage load pipeline (1, 2, 3, 4+
+    tiles), with every row recomputed and with a handful of rows (so that one of the two wave
+    groups of a workgroup, or most of its waves, own no column)."""
+    for (H_q, H_kv, d_h, picks) in ((4, 2, 128, "all"), (8, 1, 64, "few"), (2, 2, 128, "few")):
+        rng = np.random.default_rng(N * 7 + H_q)
+        model = ModelShape(H_q * d_h, H_q, H_kv, d_h, 64, 1e4, 1e-5, False, 1)
+        idx = np.arange(N) if picks == "all" else np.unique(np.r_[0, rng.integers(0, N, size=3), N - 1])
+        M = len(idx)
+        qb = gen.f32_to_bf16_bits((rng.standard_normal((M, H_q, d_h)) * 2.0).astype(np.float32))
+        Kb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+        Vb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+        ctx = _ctx(model, N, M)
+        o = torch.full((M, H_q * d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+        ctx.step_sparse_attention(dev_bf16(qb).view(M, -1), M, dev_i32(idx),
+                                  cc.KVLayer(dev_bf16(Kb), dev_bf16(Vb)), o, _lib.FLAG_CHECK_IDX)
+        torch.cuda.synchronize()
+        qf, Kf, Vf = obf.bits_to_f64(qb), obf.bits_to_f64(Kb), obf.bits_to_f64(Vb)
+        ref = np.stack([layer.attend_row(qf[i], Kf, Vf, int(idx[i]), H_q // H_kv)[0].reshape(-1)
+                        for i in range(M)])
+        mx, mn = err_stats(bits_f64(host_bits(o)), ref)
+        assert mx <= MAX_ABS and mn <= MEAN_ABS, (N, H_q, H_kv, d_h, picks, mx, mn)
+        ctx.close()
+
+
+def test_stage_attention_many_column_blocks_long_and_short_rows():
+    """Several 256-column blocks per kv head whose rows end at very different keys: within a
+    block the waves stop at different tiles while the block keeps loading."""
+    H_q, H_kv, d_h, N = 8, 2, 128, 1500
+    rng = np.random.default_rng(5)
+    model = ModelShape(H_q * d_h, H_q, H_kv, d_h, 64, 1e4, 1e-5, False, 1)
+    idx = np.unique(np.r_[np.arange(0, 40), rng.integers(40, N, size=200), np.arange(N - 30, N)])
+    M = len(idx)
+    qb = gen.f32_to_bf16_bits((rng.standard_normal((M, H_q, d_h)) * 2.0).astype(np.float32))
+    Kb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+    Vb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+    ctx = _ctx(model, N, M)
+    o = torch.full((M, H_q * d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ctx.step_sparse_attention(dev_bf16(qb).view(M, -1), M, dev_i32(idx),
+                              cc.KVLayer(dev_bf16(Kb), dev_bf16(Vb)), o, _lib.FLAG_CHECK_IDX)
+    torch.cuda.synchronize()
+    qf, Kf, Vf = obf.bits_to_f64(qb), obf.bits_to_f64(Kb), obf.bits_to_f64(Vb)
+    rows = np.unique(np.r_[np.arange(0, 12), rng.integers(0, M, size=40), np.arange(M - 12, M)])
+    ref = np.stack([layer.attend_row(qf[i], Kf, Vf, int(idx[i]), H_q // H_kv)[0].reshape(-1) for i in rows])
+    mx, mn = err_stats(bits_f64(host_bits(o)[rows]), ref)
+    assert np.isfinite(bits_f64(host_bits(o))).all()
+    assert mx <= MAX_ABS and mn <= MEAN_ABS, (mx, mn)
+    ctx.close()
+
+
 def test_stage_projections_against_oracle_pieces():
     model = ModelShape(512, 8, 2, 64, 768, 1e4, 1e-5, True, 1)
     N, M = 500, 203
