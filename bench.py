@@ -94,6 +94,13 @@ def hbm_kernels_c5(dev, reps=20):
     cV = [torch.randn((wl.P + L,) + row, dtype=torch.float32, device=dev).to(torch.bfloat16) for L in wl.chunk_lens]
     dst = cc.KVLayer(torch.empty((wl.N,) + row, dtype=torch.bfloat16, device=dev),
                      torch.empty((wl.N,) + row, dtype=torch.bfloat16, device=dev))
+    # scores from batched per-chunk attention tensors, C3 request: 16 x (chunk + query) of a
+    # 14-head auxiliary model, [14, 128, 64 + 1024 + 128] fp32 each
+    w3 = CONFIGS["C3"]
+    aux_h = 14
+    raw = [(torch.rand((aux_h, w3.Q_a, w3.P + L + w3.Q_a), dtype=torch.float32, device=dev), w3.P, L)
+           for L in w3.chunk_lens]
+    score3 = torch.empty(w3.T, dtype=torch.float32, device=dev)
     ctx.profile_enable(True)
     ctx_a.profile_enable(True)
     for it in range(reps + 2):
@@ -104,15 +111,18 @@ def hbm_kernels_c5(dev, reps=20):
         ctx.step_gather_rmsnorm(hidden, idx, M, w, xn)
         ctx_a.assemble_cache(cK, cV, wl.P, wl.Q, dst)
         ctx.calib_copy(dst.V, dst.K)          # plain copy of 135 MB: what a streaming kernel reaches here
+        ctx.step_block_scores(raw, score3)
     prof = ctx.profile_read()
     prof["assemble"] = ctx_a.profile_read()["assemble"]
     ctx.close()
     ctx_a.close()
     row_bytes = m.H_kv * m.d_h * 2
     work = {"colsum": wl.Q_a * wl.T * 4 + wl.T * 4, "gather_norm": M * m.d * 2 * 2,
-            "assemble": 2 * row_bytes * ((wl.P + wl.T) + wl.N), "copy": 2 * row_bytes * wl.N}
+            "assemble": 2 * row_bytes * ((wl.P + wl.T) + wl.N), "copy": 2 * row_bytes * wl.N,
+            "block_scores": aux_h * w3.Q_a * w3.T * 4 + w3.T * 4}
     out = {"shape": f"C5: A[{wl.Q_a},{wl.T}] fp32; gather {M} of {wl.N} rows, d={m.d}; "
-                    f"assemble {len(wl.chunk_lens)} chunk caches into [{wl.N},{m.H_kv},{m.d_h}] K and V"}
+                    f"assemble {len(wl.chunk_lens)} chunk caches into [{wl.N},{m.H_kv},{m.d_h}] K and V; "
+                    f"block_scores: C3 request, {len(w3.chunk_lens)} tensors [{aux_h},{w3.Q_a},P+L+Q_a] fp32"}
     for k, nbytes in work.items():
         ms, cnt = prof[k]
         avg = ms / cnt

@@ -125,6 +125,41 @@ cc_status cc_select(cc_ctx* ctx, const float* attn, int32_t Q_a, int32_t T, int6
                     int32_t idx_offset, int32_t n_tail,
                     int32_t* idx_out, int32_t* n_out, int32_t* n_out_host);
 
+/* One batch element of the auxiliary model's last-layer attention (Section 4.2:
+ * the chunks are processed as `chunk c + query` in one batch): fp32 attention
+ * weights with the query tokens as rows.  Element (head h, query row q, key
+ * column col) is attn[h*stride_head + q*stride_row + col] (strides in elements,
+ * device memory, read only).  The query -> chunk block is columns col0 ..
+ * col0 + len - 1: whatever lies before it (a shared prefix) and behind it (the
+ * query tokens themselves) is excluded, as the paper prescribes. */
+typedef struct cc_aux_block {
+    const float* attn;
+    int64_t stride_head;
+    int64_t stride_row;
+    int32_t col0;
+    int32_t len;            /* chunk tokens, >= 1 */
+} cc_aux_block;
+
+/* Importance scores from the batched attention tensors (Section 4.2; head average
+ * as in Section 3, then the reduction over the query dimension):
+ *   score[t0_c + j] = sum_q ( (sum_h attn_c[h][q][col0_c + j]) * (1/H) ),
+ * t0_c = len_0 + ... + len_{c-1}; fp32, heads and rows added in ascending order
+ * with one accumulator each (reproducible bit pattern).
+ *   blocks  host array of n_blocks descriptors (read during the call only)
+ *   H, Q_a  heads and query rows of every block, >= 1
+ *   score   dev fp32 [sum of len]
+ * Enqueues on the context's stream; no host synchronisation. */
+cc_status cc_step_block_scores(cc_ctx* ctx, const cc_aux_block* blocks, int32_t n_blocks, int32_t H,
+                               int32_t Q_a, float* score);
+
+/* cc_select with the scores taken from the batched attention tensors
+ * (cc_step_block_scores, T = sum of len <= T_cap) instead of a [Q_a, T] block.
+ * Other arguments, outputs and errors as for cc_select. */
+cc_status cc_select_blocks(cc_ctx* ctx, const cc_aux_block* blocks, int32_t n_blocks, int32_t H,
+                           int32_t Q_a, uint32_t recomp_bp, int32_t window, int32_t tau,
+                           int32_t flags, int32_t idx_offset, int32_t n_tail, int32_t* idx_out,
+                           int32_t* n_out, int32_t* n_out_host);
+
 /* First stage of cc_select on its own: score dev fp32 [T] (Section 4.2, reduction
  * over the query dimension). */
 cc_status cc_step_column_scores(cc_ctx* ctx, const float* attn, int32_t Q_a, int32_t T,
@@ -201,7 +236,8 @@ cc_status cc_assemble_cache(cc_ctx* ctx, const cc_chunk_kv* chunks, int32_t n_ch
 /* ---- timing of the library's own kernels on its stream ---- */
 enum {
     CC_K_COLSUM = 0, CC_K_SELECT, CC_K_GATHER_NORM, CC_K_QKV, CC_K_ATTN, CC_K_OPROJ,
-    CC_K_POST_NORM, CC_K_GATE_UP, CC_K_DOWN, CC_K_ASSEMBLE, CC_K_COPY, CC_K_COUNT
+    CC_K_POST_NORM, CC_K_GATE_UP, CC_K_DOWN, CC_K_ASSEMBLE, CC_K_COPY, CC_K_BLOCK_SCORES,
+    CC_K_COUNT
 };
 /* While enabled, every kernel launch is bracketed by HIP events on the stream. */
 cc_status cc_profile_enable(cc_ctx* ctx, int32_t on);

@@ -14,7 +14,12 @@ Readings taken where the paper is silent (all listed in the design notes):
     to the same threshold; windows ignore chunk boundaries;
   * tau = ceil(5 w / 8) when not given (5 at the paper's default w = 8);
   * grouping neither trims nor pads the result to the ratio;
-  * the user-query slots are always appended (they have no precomputed KV).
+  * the user-query slots are always appended (they have no precomputed KV);
+  * scores taken from the batched per-chunk attention tensors: heads are averaged
+    first (Section 3 works with head-averaged maps; Section 4.2 does not say), as
+    the ascending fp32 sum over heads times the fp32 value of 1/H, then the
+    query rows are summed as above.  How the head mean is rounded is not fixed
+    by the paper: parity unpinned beyond the pins of block_scores below.
 """
 from __future__ import annotations
 
@@ -35,6 +40,39 @@ def column_scores(attn: np.ndarray) -> np.ndarray:
     for q in range(attn.shape[0]):
         s = s + attn[q]          # elementwise fp32 add: one accumulator per column
     return s
+
+
+def block_scores(blocks) -> np.ndarray:
+    """Importance scores from the auxiliary model's batched last-layer attention
+    (Section 4.2): ``blocks`` is a sequence of (A, col0, length) with A of shape
+    [heads, query rows, key columns] for `chunk c + query`; the query->chunk
+    block is columns col0 .. col0+length-1 (prefix columns before it and the
+    query's own columns behind it are left out).  Per chunk token: mean over
+    heads, then sum over query rows; the chunks' scores are concatenated."""
+    out = []
+    for A, col0, length in blocks:
+        A = np.asarray(A, dtype=np.float32)
+        H, Q_a = A.shape[0], A.shape[1]
+        inv_h = np.float32(1.0) / np.float32(H)
+        s = np.zeros(length, dtype=np.float32)
+        for q in range(Q_a):
+            m = np.zeros(length, dtype=np.float32)
+            for h in range(H):
+                m = m + A[h, q, col0:col0 + length]     # fp32, ascending head
+            s = s + m * inv_h                           # fp32, ascending query row
+        out.append(s)
+    return np.concatenate(out)
+
+
+def select_from_scores(s: np.ndarray, recomp_bp: int, window: int, tau: int = 0,
+                       grouping: bool = True, idx_offset: int = 0, n_tail: int = 0) -> np.ndarray:
+    """Top-k, grouping and output of ``select`` for a given score vector."""
+    T = s.shape[0]
+    cand = top_k_candidates(s, candidate_count(T, recomp_bp))
+    chosen = group_windows(cand, window, tau if tau > 0 else default_tau(window)) if grouping else cand
+    rel = np.nonzero(chosen)[0]
+    tail = idx_offset + T + np.arange(n_tail)
+    return np.concatenate([rel + idx_offset, tail]).astype(np.int32)
 
 
 def candidate_count(T: int, recomp_bp: int) -> int:

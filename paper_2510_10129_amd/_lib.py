@@ -16,13 +16,14 @@ CC_OK = 0
 CC_ERR_NULL, CC_ERR_SHAPE, CC_ERR_IDX, CC_ERR_WORKSPACE, CC_ERR_HIP = -1, -2, -3, -4, -5
 FLAG_NO_GROUPING, FLAG_CHECK_IDX = 1, 2
 K_NAMES = ("colsum", "select", "gather_norm", "qkv", "attn", "oproj", "post_norm", "gate_up", "down",
-           "assemble", "copy")
+           "assemble", "copy", "block_scores")
 
 EXPORTS = (
     "cc_create", "cc_destroy", "cc_set_stream", "cc_last_error", "cc_select",
     "cc_step_column_scores", "cc_recompute_layer", "cc_step_gather_rmsnorm",
     "cc_step_qkv_rope_scatter", "cc_step_sparse_attention", "cc_step_oproj_residual",
     "cc_step_mlp", "cc_profile_enable", "cc_profile_read", "cc_calib_copy", "cc_assemble_cache",
+    "cc_step_block_scores", "cc_select_blocks",
 )
 
 
@@ -45,6 +46,11 @@ class _KV(C.Structure):
 
 class _Chunk(C.Structure):
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("len", C.c_int32)]
+
+
+class _AuxBlock(C.Structure):
+    _fields_ = [("attn", C.c_void_p), ("stride_head", C.c_int64), ("stride_row", C.c_int64),
+                ("col0", C.c_int32), ("len", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -92,6 +98,9 @@ def load_library() -> C.CDLL:
     lib.cc_step_mlp.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
     lib.cc_calib_copy.argtypes = [vp, vp, vp, i64]
     lib.cc_assemble_cache.argtypes = [vp, C.POINTER(_Chunk), i32, i32, i64, i64, i32, C.POINTER(_KV)]
+    lib.cc_step_block_scores.argtypes = [vp, C.POINTER(_AuxBlock), i32, i32, i32, vp]
+    lib.cc_select_blocks.argtypes = [vp, C.POINTER(_AuxBlock), i32, i32, i32, u32, i32, i32, i32, i32, i32,
+                                     vp, vp, C.POINTER(i32)]
     lib.cc_profile_enable.argtypes = [vp, i32]
     lib.cc_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     for name in EXPORTS:
@@ -190,6 +199,45 @@ class Context:
         Q_a, T = attn.shape
         self._check(self._lib.cc_step_column_scores(self._h, attn.data_ptr(), Q_a, T, attn.stride(0),
                                                     score.data_ptr()))
+
+    @staticmethod
+    def _aux_blocks(blocks):
+        """blocks: sequence of (attn cuda fp32 [H, Q_a, W], col0, len)."""
+        arr = (_AuxBlock * len(blocks))()
+        H = Q_a = None
+        for i, (a, col0, ln) in enumerate(blocks):
+            if a.dim() != 3 or a.stride(2) != 1:
+                raise ValueError("a block must be [H, Q_a, W] with unit column stride")
+            if H is None:
+                H, Q_a = a.shape[0], a.shape[1]
+            elif (a.shape[0], a.shape[1]) != (H, Q_a):
+                raise ValueError("all blocks must have the same H and Q_a")
+            if col0 + ln > a.shape[2]:
+                raise ValueError("col0 + len exceeds the block's width")
+            arr[i] = _AuxBlock(a.data_ptr(), a.stride(0), a.stride(1), col0, ln)
+        return arr, H, Q_a
+
+    def step_block_scores(self, blocks, score):
+        arr, H, Q_a = self._aux_blocks(blocks)
+        self._check(self._lib.cc_step_block_scores(self._h, arr, len(blocks), H, Q_a, score.data_ptr()))
+
+    def select_blocks(self, blocks, recomp_bp: int, window: int, tau: int = 0, flags: int = 0,
+                      idx_offset: int = 0, n_tail: int = 0, idx_out=None, n_out=None,
+                      sync: bool = True) -> Tuple["object", Optional[int]]:
+        """blocks: sequence of (attn cuda fp32 [H, Q_a, W], col0, len).  Returns (idx_out, count or None)."""
+        import torch
+        arr, H, Q_a = self._aux_blocks(blocks)
+        T = sum(b[2] for b in blocks)
+        dev = blocks[0][0].device
+        if idx_out is None:
+            idx_out = torch.empty(T + n_tail, dtype=torch.int32, device=dev)
+        if n_out is None:
+            n_out = torch.empty(1, dtype=torch.int32, device=dev)
+        host = C.c_int32(-1)
+        self._check(self._lib.cc_select_blocks(self._h, arr, len(blocks), H, Q_a, recomp_bp, window, tau,
+                                               flags, idx_offset, n_tail, idx_out.data_ptr(),
+                                               n_out.data_ptr(), C.byref(host) if sync else None))
+        return idx_out, (host.value if sync else None)
 
     # ---- layer ----
     def recompute_layer(self, hidden, gather_idx, kv: KVLayer, idx, M: int, w: LayerWeights, out,

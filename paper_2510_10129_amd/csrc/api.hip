@@ -177,6 +177,77 @@ cc_status cc_step_column_scores(cc_ctx* c, const float* attn, int32_t Q_a, int32
     return CC_OK;
 }
 
+// Validates the descriptors, enqueues the block-score launches (CC_BLK_SEGS batch elements
+// each) and returns the number of scores in *T_out.
+static cc_status block_scores(cc_ctx* c, const cc_aux_block* blocks, int32_t n_blocks, int32_t H,
+                              int32_t Q_a, int64_t T_max, float* score, int32_t* T_out) {
+    if (!blocks || !score) return fail(c, CC_ERR_NULL, "blocks and score must not be NULL");
+    if (n_blocks < 1 || H < 1 || Q_a < 1) return fail(c, CC_ERR_SHAPE, "need n_blocks >= 1, H >= 1, Q_a >= 1");
+    int64_t T = 0;
+    for (int i = 0; i < n_blocks; ++i) {
+        const cc_aux_block& b = blocks[i];
+        if (!b.attn) return fail(c, CC_ERR_NULL, "a block's attn must not be NULL");
+        if (b.len < 1 || b.col0 < 0 || b.stride_row < (int64_t)b.col0 + b.len ||
+            b.stride_head < (int64_t)(Q_a - 1) * b.stride_row + b.col0 + b.len)
+            return fail(c, CC_ERR_SHAPE, "a block needs len >= 1, col0 >= 0, stride_row >= col0 + len and non-overlapping heads");
+        T += b.len;
+        if (T > T_max) return fail(c, T_max == (int64_t)c->m.T_cap ? CC_ERR_WORKSPACE : CC_ERR_SHAPE, "sum of len exceeds the score capacity");
+    }
+    int32_t t0 = 0;
+    for (int i0 = 0; i0 < n_blocks; i0 += CC_BLK_SEGS) {
+        cc_blk_args a;
+        a.n_seg = std::min<int>(CC_BLK_SEGS, n_blocks - i0);
+        a.n_blocks = 0;
+        for (int i = 0; i < a.n_seg; ++i) {
+            const cc_aux_block& b = blocks[i0 + i];
+            a.seg[i] = cc_blk_seg{b.attn, b.stride_head, b.stride_row, b.col0, b.len, t0, a.n_blocks};
+            a.n_blocks += (b.len + 63) / 64;
+            t0 += b.len;
+        }
+        cc_prof_scope ps(c, CC_K_BLOCK_SCORES);
+        cc_launch_block_scores(a, H, Q_a, score, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    *T_out = (int32_t)T;
+    return CC_OK;
+}
+
+cc_status cc_step_block_scores(cc_ctx* c, const cc_aux_block* blocks, int32_t n_blocks, int32_t H,
+                               int32_t Q_a, float* score) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    int32_t T = 0;
+    return block_scores(c, blocks, n_blocks, H, Q_a, INT32_MAX, score, &T);
+}
+
+cc_status cc_select_blocks(cc_ctx* c, const cc_aux_block* blocks, int32_t n_blocks, int32_t H,
+                           int32_t Q_a, uint32_t recomp_bp, int32_t window, int32_t tau,
+                           int32_t flags, int32_t idx_offset, int32_t n_tail, int32_t* idx_out,
+                           int32_t* n_out, int32_t* n_out_host) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!idx_out || !n_out) return fail(c, CC_ERR_NULL, "idx_out and n_out must not be NULL");
+    if (recomp_bp > 10000u) return fail(c, CC_ERR_SHAPE, "recomp_bp must be <= 10000");
+    if (window < 1 || window > 1024) return fail(c, CC_ERR_SHAPE, "window must be in [1, 1024]");
+    if (tau < 0 || tau > window) return fail(c, CC_ERR_SHAPE, "tau must be in [0, window]");
+    if (n_tail < 0 || idx_offset < 0) return fail(c, CC_ERR_SHAPE, "idx_offset and n_tail must be >= 0");
+    int32_t T = 0;
+    cc_status st = block_scores(c, blocks, n_blocks, H, Q_a, c->m.T_cap, c->score, &T);
+    if (st != CC_OK) return st;
+    const int k = (int)(((int64_t)T * (int64_t)recomp_bp) / 10000);
+    const int tau_eff = tau > 0 ? tau : (5 * window + 7) / 8;
+    {
+        cc_prof_scope ps(c, CC_K_SELECT);
+        cc_launch_select(c->score, T, k, window, tau_eff, (flags & CC_FLAG_NO_GROUPING) ? 0 : 1,
+                         idx_offset, n_tail, idx_out, n_out, c->stream);
+    }
+    CC_HIP(c, hipGetLastError());
+    if (n_out_host) {
+        CC_HIP(c, hipMemcpyAsync(c->pinned + 1, n_out, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        CC_HIP(c, hipStreamSynchronize(c->stream));
+        *n_out_host = c->pinned[1];
+    }
+    return CC_OK;
+}
+
 cc_status cc_select(cc_ctx* c, const float* attn, int32_t Q_a, int32_t T, int64_t ld,
                     uint32_t recomp_bp, int32_t window, int32_t tau, int32_t flags,
                     int32_t idx_offset, int32_t n_tail, int32_t* idx_out, int32_t* n_out,

@@ -75,6 +75,20 @@ struct cc_asm_args {
 };
 void cc_launch_assemble(const cc_asm_args& a, const float2* rope, const cc_model_desc& m,
                         int64_t src_st, int64_t src_sh, const cc_kv_layer& dst, hipStream_t s);
+// One launch of the block-score kernel covers up to CC_BLK_SEGS batch elements.
+#define CC_BLK_SEGS 64
+struct cc_blk_seg {
+    const float* attn;      // element (h, q, col) at attn[h*stride_head + q*stride_row + col]
+    int64_t stride_head, stride_row;
+    int32_t col0, len;      // query -> chunk block: columns col0 .. col0 + len - 1
+    int32_t t0;             // first score it produces
+    int32_t blk0;           // first workgroup (64 columns each) of this element within the launch
+};
+struct cc_blk_args {
+    cc_blk_seg seg[CC_BLK_SEGS];
+    int32_t n_seg, n_blocks;
+};
+void cc_launch_block_scores(const cc_blk_args& a, int H, int Q_a, float* score, hipStream_t s);
 void cc_launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t s);
 void cc_launch_rope_table(float2* table, int n_pos, int d_h, double base, hipStream_t s);
 void cc_launch_colsum(const float* attn, int Q_a, int T, int64_t ld, float* score, hipStream_t s);

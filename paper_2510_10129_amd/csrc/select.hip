@@ -63,6 +63,88 @@ void cc_launch_colsum(const float* attn, int Q_a, int T, int64_t ld, float* scor
 }
 
 // ----------------------------------------------------------------------------
+// Importance scores straight from the auxiliary model's batched last-layer
+// attention (Section 4.2): batch element c holds the attention of `chunk c +
+// query`, [head][query row][key column]; the query -> chunk block starts at
+// column col0 and is len columns wide.  Heads are averaged (the attention maps
+// of Section 3 are head averages), then the query rows are summed:
+//     a(q, j) = (sum over heads, ascending, of A[h][q][col0 + j]) * (1 / H)
+//     s(t0 + j) = sum over q, ascending, of a(q, j)
+// all in fp32 with one accumulator each, so the result has one bit pattern.
+// Same scheme as the column sum above with more loads in flight (a request has
+// only T / 64 workgroups): sixteen waves own 64 columns of one batch element,
+// wave w forms a(q, .) for four of every 64 query rows (the loads of four rows
+// x eight heads are issued together), parks them in LDS, and wave 0 adds the 64
+// parked values of its column in order.
+// ----------------------------------------------------------------------------
+#define BS_WAVES 16
+#define BS_RPW (CS_ROWS / BS_WAVES)
+__global__ __launch_bounds__(64 * BS_WAVES) void block_scores_kernel(cc_blk_args a, int H, int Q_a, float inv_h,
+                                                                     float* __restrict__ score) {
+    __shared__ float tile[2][CS_ROWS][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int blk = blockIdx.x;
+    int lo = 0, hi = a.n_seg - 1, sidx = 0;
+    while (lo <= hi) {                      // last segment whose first workgroup is <= blk
+        const int mid = (lo + hi) >> 1;
+        if (a.seg[mid].blk0 <= blk) { sidx = mid; lo = mid + 1; } else { hi = mid - 1; }
+    }
+    const cc_blk_seg sg = a.seg[sidx];
+    const int j = (blk - sg.blk0) * 64 + lane;
+    const bool col_ok = j < sg.len;
+    const float* p = sg.attn + sg.col0 + (col_ok ? j : 0);
+    float acc = 0.0f;
+    const int n_groups = (Q_a + CS_ROWS - 1) / CS_ROWS;
+    for (int c = 0; c < n_groups; ++c) {
+        const int q0 = c * CS_ROWS + wave * BS_RPW;
+        float (*buf)[64] = tile[c & 1];
+        const float* pq[BS_RPW];
+        float m[BS_RPW];
+#pragma unroll
+        for (int u = 0; u < BS_RPW; ++u) {      // rows past the end re-read the last row and are not summed
+            pq[u] = p + (int64_t)min(q0 + u, Q_a - 1) * sg.stride_row;
+            m[u] = 0.0f;
+        }
+        for (int h0 = 0; h0 < H; h0 += 8) {
+            float v[BS_RPW][8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {       // heads past the end re-read the last head and are not added
+                const int64_t ho = (int64_t)min(h0 + i, H - 1) * sg.stride_head;
+#pragma unroll
+                for (int u = 0; u < BS_RPW; ++u) v[u][i] = __builtin_nontemporal_load(pq[u] + ho);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int u = 0; u < BS_RPW; ++u) m[u] = h0 + i < H ? m[u] + v[u][i] : m[u];
+        }
+#pragma unroll
+        for (int u = 0; u < BS_RPW; ++u) buf[wave * BS_RPW + u][lane] = m[u] * inv_h;
+        // the buffer written now was last read two groups ago; one barrier per group
+        // orders both that reuse and this hand-over
+        __syncthreads();
+        if (wave == 0) {
+            const int rows = min(CS_ROWS, Q_a - c * CS_ROWS);
+            int r = 0;
+            for (; r + 8 <= rows; r += 8) {
+                float x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = buf[r + u][lane];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc = acc + x[u];
+            }
+            for (; r < rows; ++r) acc = acc + buf[r][lane];
+        }
+    }
+    if (wave == 0 && col_ok) score[sg.t0 + j] = acc;
+}
+
+void cc_launch_block_scores(const cc_blk_args& a, int H, int Q_a, float* score, hipStream_t s) {
+    if (a.n_blocks <= 0) return;
+    hipLaunchKernelGGL(block_scores_kernel, dim3(a.n_blocks), dim3(64 * BS_WAVES), 0, s, a, H, Q_a, 1.0f / (float)H, score);
+}
+
+// ----------------------------------------------------------------------------
 // Top-k + grouping + compaction in one workgroup of 16 waves.
 //
 // Scores become order-preserving 32-bit keys; the k-th largest key is found by

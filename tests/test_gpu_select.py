@@ -113,3 +113,73 @@ def test_argument_errors(ctx):
         small.select(A, 100, 8)
     assert e.value.status == _lib.CC_ERR_WORKSPACE
     small.close()
+
+
+# ------------------------------------------------- scores from batched per-chunk attention
+def _dev_blocks(blocks_np, pad_rows=0, pad_cols=0):
+    """Device copies; with padding the blocks become strided views of larger tensors."""
+    out = []
+    for A, c0, L in blocks_np:
+        H, Qa, W = A.shape
+        big = torch.full((H, Qa + pad_rows, W + pad_cols), 123.0, dtype=torch.float32, device=DEV)
+        big[:, :Qa, :W] = torch.from_numpy(A).to(DEV)
+        out.append((big[:, :Qa, :W], c0, L))
+    return out
+
+
+@pytest.mark.parametrize("H,Qa,P,lens", [
+    (1, 1, 0, [1]),
+    (3, 5, 4, [63, 64, 65, 1, 200]),
+    (14, 33, 16, [300, 17, 511]),
+    (16, 128, 64, [1024, 777]),
+    (28, 70, 8, [129] * 5),
+    (9, 64, 0, [40] * 70),            # more batch elements than one launch takes
+])
+def test_block_scores_bit_exact(ctx, H, Qa, P, lens):
+    rng = np.random.default_rng(H * 1000 + Qa)
+    blocks = [(rng.random((H, Qa, P + L + Qa), dtype=np.float32), P, L) for L in lens]
+    ref = osel.block_scores(blocks)
+    for pad in (0, 3):
+        score = torch.full((sum(lens),), -1.0, dtype=torch.float32, device=DEV)
+        ctx.step_block_scores(_dev_blocks(blocks, pad, pad), score)
+        torch.cuda.synchronize()
+        assert np.array_equal(score.cpu().numpy().view(np.uint32), ref.view(np.uint32)), (H, Qa, pad)
+
+
+def test_select_blocks_matches_oracle(ctx):
+    rng = np.random.default_rng(11)
+    for H, Qa, P, lens, bp, w in ((4, 16, 8, [256] * 4, 2000, 8), (14, 32, 16, [300, 100, 511, 77], 1000, 16),
+                                  (2, 3, 0, [50], 5000, 4)):
+        # peaked rows: a few columns carry most of the weight, with ties across heads
+        blocks = []
+        for L in lens:
+            A = rng.random((H, Qa, P + L + Qa), dtype=np.float32) * 0.01
+            hot = rng.integers(P, P + L, size=max(1, L // 10))
+            A[:, :, hot] += rng.integers(1, 4, size=(1, 1, len(hot))).astype(np.float32) * 0.25
+            blocks.append((A, P, L))
+        s = osel.block_scores(blocks)
+        for grouping in (True, False):
+            ref = osel.select_from_scores(s, bp, w, 0, grouping, P, Qa)
+            idx, n = ctx.select_blocks(_dev_blocks(blocks), bp, w, 0, 0 if grouping else _lib.FLAG_NO_GROUPING, P, Qa)
+            assert n == len(ref) and np.array_equal(idx[:n].cpu().numpy(), ref)
+
+
+def test_block_scores_argument_errors(ctx):
+    A = torch.zeros((2, 4, 40), dtype=torch.float32, device=DEV)
+    score = torch.zeros(64, dtype=torch.float32, device=DEV)
+    with pytest.raises(ValueError):
+        ctx.step_block_scores([(A, 30, 20)], score)                     # block runs past its width
+    with pytest.raises(ValueError):
+        ctx.step_block_scores([(A, 0, 10), (A[:1], 0, 10)], score)      # differing head counts
+    arr = (_lib._AuxBlock * 1)(_lib._AuxBlock(A.data_ptr(), A.stride(0), A.stride(1), 0, 0))
+    assert ctx._lib.cc_step_block_scores(ctx._h, arr, 1, 2, 4, score.data_ptr()) == _lib.CC_ERR_SHAPE   # len 0
+    arr = (_lib._AuxBlock * 1)(_lib._AuxBlock(A.data_ptr(), A.stride(0), 10, 0, 20))
+    assert ctx._lib.cc_step_block_scores(ctx._h, arr, 1, 2, 4, score.data_ptr()) == _lib.CC_ERR_SHAPE   # rows overlap
+    arr = (_lib._AuxBlock * 1)(_lib._AuxBlock(None, A.stride(0), A.stride(1), 0, 20))
+    assert ctx._lib.cc_step_block_scores(ctx._h, arr, 1, 2, 4, score.data_ptr()) == _lib.CC_ERR_NULL
+    small = cc.Context(d=256, H_q=4, H_kv=2, d_h=64, f=1024, rope_base=1e4, rms_eps=1e-5,
+                       N_cap=64, M_cap=8, T_cap=32)
+    with pytest.raises(cc.CacheClipError) as e:
+        small.select_blocks([(A, 0, 40)], 1000, 8)
+    assert e.value.status == _lib.CC_ERR_WORKSPACE
+    small.close()

@@ -186,3 +186,57 @@ def test_select_on_tiny_config_properties():
     for st in np.nonzero(passing)[0]:
         marked[st:st + wl.window] = True
     assert idx[:-wl.Q].tolist() == (np.nonzero(marked)[0] + wl.P).tolist()
+
+
+# ------------------------------------------------- scores from batched per-chunk attention
+def _raw_blocks(rng, H, Q_a, lens, P, pad=0):
+    blocks = []
+    for L in lens:
+        W = P + L + Q_a + pad
+        A = rng.random((H, Q_a, W), dtype=np.float32)
+        blocks.append((A, P, L))
+    return blocks
+
+
+def test_block_scores_closed_forms_and_exclusions():
+    rng = np.random.default_rng(0)
+    # all ones, power-of-two head count: head mean is exactly 1, the score exactly Q_a
+    ones = [(np.ones((8, 5, 40), np.float32), 7, 20), (np.ones((8, 5, 33), np.float32), 7, 11)]
+    s = osel.block_scores(ones)
+    assert s.shape == (31,) and np.all(s == 5.0)
+    # a single head: the head mean is the block itself, so the scores are the column sums
+    b1 = _raw_blocks(rng, 1, 9, [17, 64, 3], 4)
+    ref = np.concatenate([osel.column_scores(A[0][:, c0:c0 + L]) for A, c0, L in b1])
+    assert np.array_equal(osel.block_scores(b1), ref)
+    # what lies outside the query->chunk block (prefix and query columns) does not matter
+    b2 = _raw_blocks(rng, 3, 6, [10, 25], 5)
+    base = osel.block_scores(b2)
+    for A, c0, L in b2:
+        A[:, :, :c0] = 99.0
+        A[:, :, c0 + L:] = -7.0
+    assert np.array_equal(osel.block_scores(b2), base)
+    # chunks are concatenated in order
+    assert np.array_equal(osel.block_scores(b2[::-1]), np.concatenate([base[10:], base[:10]]))
+
+
+def test_block_scores_match_float64_mean_then_sum():
+    rng = np.random.default_rng(1)
+    for H, Q_a in ((3, 7), (14, 33), (16, 128), (28, 5)):
+        blocks = _raw_blocks(rng, H, Q_a, [50, 129], 6)
+        got = osel.block_scores(blocks).astype(np.float64)
+        ref = np.concatenate([A[:, :, c0:c0 + L].astype(np.float64).mean(axis=0).sum(axis=0) for A, c0, L in blocks])
+        # fp32 accumulation of H + Q_a terms of size <= 1 and Q_a respectively
+        assert np.max(np.abs(got - ref)) <= 1e-6 * Q_a * (1 + H / 8)
+    # a head that carries weight w in one (q, column) entry adds w / H to that column only
+    A = np.zeros((4, 3, 20), np.float32)
+    A[2, 1, 9] = 0.5
+    s = osel.block_scores([(A, 2, 15)])
+    assert s[7] == np.float32(0.125) and np.count_nonzero(s) == 1
+
+
+def test_select_from_scores_equals_select():
+    rng = np.random.default_rng(2)
+    A = rng.random((6, 300), dtype=np.float32)
+    for bp, w, tau, grp in ((2000, 8, 5, True), (500, 16, 0, True), (3000, 8, 5, False)):
+        assert np.array_equal(osel.select_from_scores(osel.column_scores(A), bp, w, tau, grp, 11, 4),
+                              osel.select(A, bp, w, tau, grp, 11, 4))
