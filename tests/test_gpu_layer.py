@@ -351,6 +351,52 @@ def test_two_layer_stack_with_real_stale_caches():
     ctx.close()
 
 
+@pytest.mark.parametrize("prefix", [16, 0])
+def test_whole_request_on_the_device(prefix):
+    """A request from the offline artefacts to the last layer's output, every step on the
+    device: scores from the batched auxiliary attention tensors -> candidates -> grouping,
+    per-chunk caches assembled behind one prefix copy (or none), two layers recomputed on the
+    selected rows.  The oracle does the same from the same inputs."""
+    from oracle import select as osel
+    wl = replace(CONFIGS["C1x2"], P=prefix, chunk_lens=(256, 200, 300, 129))
+    model = wl.model
+    ws = [gen.layer_weights(model, l, wl.seed) for l in range(2)]
+    xl, _ = gen.hidden_pair(wl)
+    per = fixture.chunk_caches(xl, wl.P, wl.chunk_lens, ws, model)
+    blocks = gen.aux_attention_blocks(wl, heads=4)
+    # oracle
+    idx = osel.select_from_scores(osel.block_scores(blocks), 2000, wl.window, wl.tau, True, wl.P, wl.Q)
+    Ks, Vs = fixture.concat_caches(per, wl.P, wl.chunk_lens, wl.Q, model, 2)
+    ref = fixture.selective_prefill(xl, Ks, Vs, idx, ws, model)
+    # device
+    ctx = _ctx(model, wl.N, wl.N)
+    dblocks = [(torch.from_numpy(A).to(DEV), c0, L) for A, c0, L in blocks]
+    didx, M = ctx.select_blocks(dblocks, 2000, wl.window, wl.tau, 0, wl.P, wl.Q)
+    assert M == len(idx) and np.array_equal(didx[:M].cpu().numpy(), idx)
+    h, g = dev_bf16(xl), didx
+    for l in range(2):
+        Kd = torch.empty((wl.N, model.H_kv, model.d_h), dtype=torch.bfloat16, device=DEV)
+        Vd = torch.empty_like(Kd)
+        ctx.assemble_cache([dev_bf16(pc[0][l]) for pc in per], [dev_bf16(pc[1][l]) for pc in per],
+                           wl.P, wl.Q, cc.KVLayer(Kd, Vd))
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(Vd), Vs[l])
+        assert (host_bits(Kd) == Ks[l]).mean() > 0.995          # re-rotated keys: same value up to one rounding
+        out = torch.empty((M, model.d), dtype=torch.bfloat16, device=DEV)
+        ctx.recompute_layer(h, g, cc.KVLayer(Kd, Vd), didx, M, dev_weights(ws[l]), out, _lib.FLAG_CHECK_IDX)
+        torch.cuda.synchronize()
+        mx, mn = err_stats(bits_f64(host_bits(out)), ref[l].out)
+        print(f"request P={prefix} layer {l}: M={M} out max {mx:.2e} mean {mn:.2e}")
+        # chained on the device's own outputs and keys: one bf16 spacing of the residual
+        # stream on top of the per-layer bound (as in the stack test above)
+        assert mx <= MAX_ABS + 2.0 ** -7 * np.abs(ref[l].out).max() and mn <= MEAN_ABS
+        for name, fresh, got in (("K", ref[l].k_new, Kd), ("V", ref[l].v_new, Vd)):
+            kmx, kmn = err_stats(bits_f64(host_bits(got)[idx]), fresh)
+            assert kmx <= MAX_ABS + (2.0 ** -7 * np.abs(fresh).max() if l else 0.0) and kmn <= MEAN_ABS, (name, l, kmx, kmn)
+        h, g = out, None
+    ctx.close()
+
+
 def _sampled_layer_case(name, bp, n_rows, seed):
     wl = CONFIGS[name]
     model = replace(wl.model, n_layers=1)

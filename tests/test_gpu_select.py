@@ -183,3 +183,27 @@ def test_block_scores_argument_errors(ctx):
         small.select_blocks([(A, 0, 40)], 1000, 8)
     assert e.value.status == _lib.CC_ERR_WORKSPACE
     small.close()
+
+
+@pytest.mark.parametrize("name,prefix", [("C2", None), ("C2", 0), ("C4", None)])
+def test_blocks_window_sweep_and_no_prefix(ctx, name, prefix):
+    """Per-chunk-normalised scores from batched tensors at request size: windows 8, 16, 32,
+    grouping on and off, with and without a shared prefix, ragged chunk lengths (C4)."""
+    import dataclasses
+    wl = CONFIGS[name]
+    if name == "C4":       # a third of the request keeps the host-side generator quick
+        wl = dataclasses.replace(wl, chunk_lens=wl.chunk_lens[:10], Q_a=32)
+    blocks = gen.aux_attention_blocks(wl, heads=14 if name == "C2" else 9, prefix=prefix)
+    P = blocks[0][1]
+    s = osel.block_scores(blocks)
+    assert abs(float(s.sum()) - wl.Q_a * len(blocks)) < 0.5 * wl.Q_a * len(blocks)   # most mass sits on chunk tokens
+    dev_blocks = _dev_blocks(blocks)
+    score = torch.empty(wl.T, dtype=torch.float32, device=DEV)
+    ctx.step_block_scores(dev_blocks, score)
+    assert np.array_equal(score.cpu().numpy().view(np.uint32), s.view(np.uint32))
+    for w in (8, 16, 32):
+        for grouping in (True, False):
+            ref = osel.select_from_scores(s, 2000, w, 0, grouping, P, wl.Q)
+            idx, n = ctx.select_blocks(dev_blocks, 2000, w, 0, 0 if grouping else _lib.FLAG_NO_GROUPING, P, wl.Q)
+            assert n == len(ref) and np.array_equal(idx[:n].cpu().numpy(), ref), (name, prefix, w, grouping)
+        print(f"{name} prefix={P} w={w}: M_sel/T = {(len(osel.select_from_scores(s, 2000, w, 0, True, P, wl.Q)) - wl.Q) / wl.T:.3f}")

@@ -118,6 +118,34 @@ def aux_attention(wl: Workload) -> np.ndarray:
     return _row_softmax(z)
 
 
+def aux_attention_blocks(wl: Workload, heads: int, prefix: int | None = None):
+    """The batched form of the auxiliary model's last-layer attention (one element per
+    `chunk c + query`): list of (A fp32 [heads, Q_a, P + L_c + Q_a], col0 = P, L_c).
+    Every row is a softmax over that element's own key columns (prefix, chunk, the query's
+    causal part), so the scores are normalised per chunk.  Logits: 2*N(0,1) per head, plus
+    bumps of +4 over spans of U[4,24] chunk tokens shared by all heads and rows (about L_c/64
+    per chunk), plus +2 on the first prefix column (a sink) when there is a prefix."""
+    P = wl.P if prefix is None else prefix
+    r = _rng(wl.seed, _S_SCORES + 17)
+    Qa = wl.Q_a
+    out = []
+    for L in wl.chunk_lens:
+        W = P + L + Qa
+        z = 2.0 * r.standard_normal(size=(heads, Qa, W), dtype=np.float32).astype(np.float64)
+        for _ in range(max(1, L // 64)):
+            s0 = int(r.integers(0, L))
+            z[:, :, P + s0:P + min(L, s0 + int(r.integers(4, 25)))] += 4.0
+        if P > 0:
+            z[:, :, 0] += 2.0
+        q = np.arange(Qa)[:, None]
+        k = np.arange(W)[None, :]
+        z = np.where(k <= P + L + q, z, -np.inf)       # the query rows are causal among themselves
+        z -= z.max(axis=-1, keepdims=True)
+        e = np.exp(z)
+        out.append(((e / e.sum(axis=-1, keepdims=True)).astype(np.float32), P, int(L)))
+    return out
+
+
 def exact_ratio_idx(wl: Workload, recomp_bp: int, run: int | None = None) -> np.ndarray:
     """A hand-built recompute set of exactly floor(T*bp/10000) chunk tokens made
     of non-overlapping runs of ``run`` tokens at random starts (what grouping
