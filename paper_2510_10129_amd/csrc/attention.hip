@@ -326,17 +326,11 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     // j + PD are issued before MFMA j.  P V: MFMA j = (ss, dt) = (j / DT, j % DT), DT
     // independent accumulation chains; A slots 0..3 <- keys 16ss+4hf.., 4..7 <- keys
     // 16ss+8+4hf..  Scores: MFMA n = (ks, kt) = (n / 2, n % 2), two chains.
-#ifndef CC_ATTN_PD
-#define CC_ATTN_PD 4
-#endif
-    constexpr int PD = CC_ATTN_PD;
+    constexpr int PD = 4;
     auto matrix_phase = [&](auto with_pv) __attribute__((always_inline)) {
         constexpr int NPV = decltype(with_pv)::value ? 4 * DT : 0, NQK = 2 * KS, NALL = NPV + NQK;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         bf16x8 opnd[NALL];
-#ifdef CC_ATTN_PRIO
-        __builtin_amdgcn_s_setprio(3);
-#endif
         auto issue = [&](auto jc) __attribute__((always_inline)) {
             constexpr int j = decltype(jc)::value;
             if constexpr (j < NPV) {
@@ -367,9 +361,6 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
                 s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[j], qf[ks], ks == 0 ? zero : s[kt], 0, 0, 0);
             }
         });
-#ifdef CC_ATTN_PRIO
-        __builtin_amdgcn_s_setprio(0);
-#endif
     };
 
     // ---- phases.  P0: A scores(0).  P(2t+1): A softmax(t) | B values(t-1), scores(t).
@@ -377,13 +368,13 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     //      end of its matrix phase, while its SIMD partner is in the softmax: next to a partner
     //      that keeps the matrix pipe busy a vector-memory instruction takes several times as
     //      long to issue.  Group A loads V(t+2) at the end of P(2t+2) into the stage V(t-1)
-    //      left at the end of P(2t+1); it is first read in P(2t+6) and group A waits for it at
-    //      the end of P(2t+5), with V(t+3) still in flight.  Group B loads K(t+3) at the end of
-    //      P(2t+3) into the stage K(t) left at the end of P(2t+1); first read in P(2t+6), group
-    //      B waits for it at the end of P(2t+5), after issuing K(t+4).  Every wave passes
-    //      2 n_tiles + 3 barriers; tiles past a wave's own last key only cost it the barriers
-    //      and its loads.  The scores of tile my_tiles (computed from whatever its stage holds)
-    //      are never used.
+    //      left at the end of P(2t+1); it is first read in P(2t+6); group A lets only its newest
+    //      tile stay in flight across a barrier, so V(t+2) has landed by the end of P(2t+4).
+    //      Group B loads K(t+3) at the end of P(2t+3) into the stage K(t) left at the end of
+    //      P(2t+1); first read in P(2t+6), landed by the end of P(2t+5) (group B waits for all
+    //      but its newest tile after issuing K(t+4)).  Every wave passes 2 n_tiles + 3
+    //      barriers; tiles past a wave's own last key only cost it the barriers and its loads.
+    //      The scores of tile my_tiles (computed from whatever its stage holds) are never used.
     const int my_tiles = wave_limit < 0 ? 0 : wave_limit / BN_KEYS + 1;
     using yes = std::integral_constant<int, 1>;
     using no = std::integral_constant<int, 0>;
