@@ -45,6 +45,8 @@ def parse():
                     help="skip timing the same stack with every token recomputed (dense prefill on the same kernels)")
     ap.add_argument("--no-hbm-extra", action="store_true",
                     help="skip timing the HBM-bound kernels at the C5 shape (where they run long enough to measure)")
+    ap.add_argument("--hbm-only", action="store_true",
+                    help="run only the HBM-bound kernels at the C5 shape and print their figures (for profiling)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one copy of 1 GiB through cc_calib_copy (for counter calibration under rocprofv3 --pmc)")
     return ap.parse_args()
@@ -202,6 +204,9 @@ def main():
         wl = replace(wl, model=model)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
+    if a.hbm_only:
+        print(json.dumps({"hbm_kernels_at_C5_shape": hbm_kernels_c5(dev)}))
+        return
 
     # ---- inputs, resident in HBM ----
     A = torch.from_numpy(gen.aux_attention(wl)).to(dev)

@@ -22,6 +22,7 @@ KINDS = (
     ("sparse_attn_kernel", "attn"), ("gather_rmsnorm_kernel", "gather_norm"),
     ("rmsnorm_f32_kernel", "post_norm"), ("colsum_kernel", "colsum"), ("select_kernel", "select"),
     ("calib_copy_kernel", "calib_copy"), ("assemble_kernel", "assemble"),
+    ("block_scores_kernel", "block_scores"),
 )
 
 
