@@ -230,6 +230,7 @@ __device__ __forceinline__ void dma16(const bf16_t* gsrc, bf16_t* lds_wave_base)
 // that share a wave base need no rewrite of M0 between them.
 template <int OFF>
 __device__ __forceinline__ void dma16_at(const char* gsrc_minus_off, bf16_t* lds_wave_base) {
+    static_assert(OFF >= 0 && OFF < 4096, "the instruction offset is 13 bits signed; a larger value wraps silently");
     __builtin_amdgcn_global_load_lds(
         (const void __attribute__((address_space(1)))*)gsrc_minus_off,
         (void __attribute__((address_space(3)))*)lds_wave_base, 16, OFF, 0);
