@@ -305,24 +305,27 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[BM / WAVES_M / 32][BN /
 }
 
 // Ring-loop epilogue.  After the K loop the four ring slots are free; each holds
-// one 32-row group of the tile as fp32 [32][BN] (exactly one slot), so a 256-row
-// tile leaves in two phases of four groups with two barriers per phase, and a
-// thread's functor calls of a phase are independent (their global loads overlap).
-// Column c of staged row r sits at c ^ 32*((r>>2)&1): the two half-waves of an
-// accumulator store (rows r and r+4) then hit disjoint banks, and 8-column
-// chunks stay contiguous for the functors.
-template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+// one RG-row group of the tile as fp32 [RG][BN] (RG = 32 where a slot is large enough,
+// else 16: half an accumulator tile), so a tile leaves in phases of four groups with two
+// barriers per phase, and a thread's functor calls of a phase are independent (their
+// global loads overlap).  Column c of staged row r sits at c ^ 32*((r>>2)&1): the two
+// half-waves of an accumulator store (rows r and r+4) then hit disjoint banks, and
+// 8-column chunks stay contiguous for the functors.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int RG, class Epi>
 __device__ __forceinline__ void store_tile_ring(f32x16 (&acc)[BM / WAVES_M / 32][BN / WAVES_N / 32],
                                                 float* s0, float* s1, float* s2, float* s3, int m0,
                                                 int bn, int M, const Epi& epi) {
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int IPP = 4 / WAVES_M;      // accumulator row blocks per wave and phase
-    constexpr int PHASES = TM / IPP;
+    constexpr int GPW = 4 / WAVES_M;      // staged groups per wave and phase
+    constexpr int VPG = RG / 2;           // accumulator registers per group and tile
+    constexpr int BPP = GPW * RG / 32;    // accumulator row blocks per wave and phase
+    constexpr int PHASES = TM / BPP;
     constexpr int TPR = BN / 8;           // threads per staged row
     constexpr int RPP = NT / TPR;         // rows per pass
-    static_assert(4 % WAVES_M == 0 && TM % IPP == 0 && 32 % RPP == 0, "epilogue shape");
+    static_assert(RG == 32 || RG == 16, "row group");
+    static_assert(4 % WAVES_M == 0 && GPW * RG % 32 == 0 && TM % BPP == 0 && RG % RPP == 0, "epilogue shape");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WAVES_M, wn0 = (wave / WAVES_M) * WN;
     const int frow = lane & 31, fk = lane >> 5;
@@ -330,17 +333,19 @@ __device__ __forceinline__ void store_tile_ring(f32x16 (&acc)[BM / WAVES_M / 32]
 #pragma unroll
     for (int p = 0; p < PHASES; ++p) {
         if (p) __syncthreads();
-        // register v of a 32x32 accumulator tile holds tile row r = 8*(v>>2) + 4*fk + (v&3);
-        // (r>>2)&1 == fk
+        // register v of a 32x32 accumulator tile holds tile row 8*(v>>2) + 4*fk + (v&3): rows
+        // 0..15 are registers 0..7, rows 16..31 registers 8..15; (row>>2)&1 == fk
 #pragma unroll
-        for (int ii = 0; ii < IPP; ++ii) {
-            const int i = p * IPP + ii;
-            float* st = stage(wm * IPP + ii);     // slot q holds wave-row q / IPP, block q % IPP
+        for (int g = 0; g < GPW; ++g) {
+            const int i = p * BPP + g * RG / 32;  // accumulator row block
+            const int sub = (g * RG % 32) / RG;   // which half of it (RG = 16)
+            float* st = stage(wm * GPW + g);      // slot q holds wave-row q / GPW, group q % GPW
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = 8 * (v >> 2) + 4 * fk + (v & 3);
+                for (int vv = 0; vv < VPG; ++vv) {
+                    const int v = sub * VPG + vv;
+                    const int r = 8 * (v >> 2) + 4 * fk + (v & 3) - sub * RG;
                     st[r * BN + ((wn0 + j * 32 + frow) ^ (fk << 5))] = acc[i][j][v];
                 }
         }
@@ -348,9 +353,9 @@ __device__ __forceinline__ void store_tile_ring(f32x16 (&acc)[BM / WAVES_M / 32]
         const int cc = (tid % TPR) * 8;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int row0 = (q / IPP) * WM + (p * IPP + q % IPP) * 32;   // tile row of the slot's first row
+            const int row0 = (q / GPW) * WM + p * BPP * 32 + (q % GPW) * RG;   // tile row of the slot's first row
 #pragma unroll
-            for (int k = 0; k < 32 / RPP; ++k) {
+            for (int k = 0; k < RG / RPP; ++k) {
                 const int r = tid / TPR + k * RPP;
                 const int m = m0 + row0 + r;
                 if (m < M) epi.template operator()<BN>(m, bn, cc, stage(q) + r * BN, ((r >> 2) & 1) << 5);
@@ -498,12 +503,19 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_I = BM / 16 / NW, B_I = BN / 16 / NW;   // DMA instructions per wave and slice
+    // DMA instructions per wave and slice.  Where the A_P 16-row pieces of A do not divide among
+    // the waves, the first A_FULL waves own A_I pieces and the others A_I - 1; those repeat
+    // their last piece so that every wave issues the same number of loads.
+    constexpr int A_P = BM / 16;
+    constexpr int A_I = (A_P + NW - 1) / NW, B_I = BN / 16 / NW;
+    constexpr int A_FULL = A_P - NW * (A_I - 1);
     constexpr int DPS = A_I + B_I;
-    constexpr int SL = (BM + BN) * BKS;
-    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0 && BN % 32 == 0, "tile/waves");
+    constexpr int SL = NW * DPS * 16 * BKS;
+    // rows of a staged fp32 group: 32 if that fits in one slot and a wave's row blocks pair up, else 16
+    constexpr int RG = (32 * BN * 4 <= SL * 2 && TM % (4 / WAVES_M) == 0) ? 32 : 16;
+    static_assert(BM % 16 == 0 && BN % (16 * NW) == 0 && BN % 32 == 0, "tile/waves");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
-    static_assert(32 * BN * 4 <= SL * 2, "a 32-row fp32 group fits in one slot");
+    static_assert(RG * BN * 4 <= SL * 2, "an fp32 row group fits in one slot");
     static_assert(DPS * (NS - 1) < 64, "vmcnt range");
 
     // One array per ring slot: the compiler then knows that a DMA into one slot
@@ -523,9 +535,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     // One DMA instruction moves 16 slice rows (16 x 64 B).  Lane L fills physical
     // chunk slot L%4 of row L/4 and fetches the logical chunk slot ^ ((row>>2)&3):
     // a 16-byte fragment read of 16 consecutive rows then touches every bank once.
-    // Wave w loads A rows w*16*A_I .. and B rows w*16*B_I .. of the tile, and a slot holds
-    // them wave by wave ([wave][A rows | B rows], DPS KB each): the DPS loads of a wave and
-    // slice share one LDS base and differ in their immediate offset only.
+    // Wave w loads its A pieces (16 rows each) and B rows w*16*B_I .. of the tile, and a slot
+    // holds them wave by wave ([wave][A rows | B rows], DPS KB each): the DPS loads of a wave
+    // and slice share one LDS base and differ in their immediate offset only.
     // Global addresses are a wave-uniform base (advanced along K in scalar
     // registers) plus a loop-invariant 32-bit lane offset.
     uint32_t ao[A_I], bo[B_I];
@@ -533,7 +545,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
     for (int i = 0; i < A_I; ++i) {
-        int r = (wave_u * A_I + i) * 16 + (lane >> 2);
+        const int piece = wave_u < A_FULL ? wave_u * A_I + i
+                                          : A_FULL * A_I + (wave_u - A_FULL) * (A_I - 1) + (i < A_I - 1 ? i : A_I - 2);
+        int r = piece * 16 + (lane >> 2);
         const int c = (lane & 3) ^ ((r >> 2) & 3);
         r = r < a_rows ? r : a_rows - 1;
         ao[i] = (uint32_t)((r * lda + c * 8) * 2);
@@ -575,9 +589,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     };
     // element offset in a slot of tile row r of A (is_b = 0) or B (is_b = 1)
     auto row_at = [](int r, int is_b) {
-        constexpr int per_a = 16 * A_I, per_b = 16 * B_I;
-        return is_b ? ((r / per_b) * DPS * 16 + A_I * 16 + r % per_b) * BKS
-                    : ((r / per_a) * DPS * 16 + r % per_a) * BKS;
+        constexpr int per_b = 16 * B_I;
+        if (is_b) return ((r / per_b) * DPS * 16 + A_I * 16 + r % per_b) * BKS;
+        const int piece = r / 16;
+        int w, i;
+        if (A_FULL == NW || piece < A_FULL * A_I) {
+            w = piece / A_I, i = piece % A_I;
+        } else {
+            const int q = piece - A_FULL * A_I;
+            w = A_FULL + q / (A_I > 1 ? A_I - 1 : 1), i = q % (A_I > 1 ? A_I - 1 : 1);
+        }
+        return (w * DPS * 16 + i * 16 + r % 16) * BKS;
     };
 
     f32x16 acc[TM][TN];
@@ -666,16 +688,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
         }
     }
     __syncthreads();   // every wave has finished reading the ring
-    store_tile_ring<BM, BN, WAVES_M, WAVES_N>(acc, reinterpret_cast<float*>(sl0), reinterpret_cast<float*>(sl1),
+    store_tile_ring<BM, BN, WAVES_M, WAVES_N, RG>(acc, reinterpret_cast<float*>(sl0), reinterpret_cast<float*>(sl1),
                                               reinterpret_cast<float*>(sl2), reinterpret_cast<float*>(sl3),
                                               m0, bn, M, epi);
 }
 
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
-// workgroup per CU), 256x128 (8 waves of 64x64, one per CU, ring loop only) and
-// 128x128 (4 waves of 64x64, two per CU, measured at 0.6 to 0.9 of the large tile's
-// rate depending on K).  A grid runs as a whole number of "rounds" of workgroups,
-// so the shape is chosen per launch to minimise rounds x tile cost.
+// workgroup per CU), 192x256 (8 waves of 96x64, ring loop only, measured at 0.8 of the
+// large tile's rate: it pays where it saves a half-empty round), 256x128 (8 waves of
+// 64x64, one per CU, ring loop only) and 128x128 (4 waves of 64x64, two per CU, measured
+// at 0.6 to 0.9 of the large tile's rate depending on K).  A grid runs as a whole number
+// of "rounds" of workgroups, so the shape is chosen per launch to minimise rounds x tile
+// cost.
 template <class BSrc, class Epi>
 void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int ldb, int gm_big,
                  BSrc bsrc, Epi epi, hipStream_t s) {
@@ -697,11 +721,14 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     bool ring = K % (BKS * NS) == 0 && (int64_t)lda * 256 * 2 < (1ll << 31) &&
                 (int64_t)ldb * 256 * 2 < (1ll << 31);
     if (force && force[0] && force[1] == 't') ring = false;
-    const double cb = cost(256, 256, 1, 1.00), ch = cost(256, 128, 1, 0.75), cs = cost(128, 128, 2, 0.72);
+    const double cb = cost(256, 256, 1, 1.00), cm = cost(192, 256, 1, 0.80), ch = cost(256, 128, 1, 0.75),
+                 cs = cost(128, 128, 2, 0.72);
     char pick = cb <= cs ? 'b' : 's';
-    if (ring && ch < (pick == 'b' ? cb : cs)) pick = 'h';       // the half-width tile has no staged variant
-    if (force && (force[0] == 'b' || force[0] == 's' || (force[0] == 'h' && ring))) pick = force[0];
-    const int bm = pick == 's' ? 128 : 256, bn = pick == 'b' ? 256 : 128;
+    double best = cb <= cs ? cb : cs;
+    if (ring && ch < best) pick = 'h', best = ch;               // these two have no staged variant
+    if (ring && cm < best) pick = 'm', best = cm;
+    if (force && (force[0] == 'b' || force[0] == 's' || ((force[0] == 'h' || force[0] == 'm') && ring))) pick = force[0];
+    const int bm = pick == 's' ? 128 : pick == 'm' ? 192 : 256, bn = (pick == 'b' || pick == 'm') ? 256 : 128;
     const int tiles_m = (M + bm - 1) / bm, tiles_n = (N_tiles_cols + bn - 1) / bn;
     int GM = pick == 's' ? 2 * gm_big : gm_big;
     if (force_gm) GM = atoi(force_gm);
@@ -713,6 +740,8 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     if (pick == 'b') {
         if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4);
         else CC_LAUNCH(gemm_nt_kernel, 256, 256, 2, 4);
+    } else if (pick == 'm') {
+        CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4);
     } else if (pick == 'h') {
         CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2);
     } else {
