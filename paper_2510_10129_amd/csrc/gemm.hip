@@ -709,8 +709,13 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
             (void)hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         return n > 0 ? n : 256;
     }();
-    static const char* force = [] { const char* e = getenv("CC_GEMM_CFG"); return (e && *e) ? e : (const char*)nullptr; }();   // "b" / "s": tile; second char "t": staged loop
-    static const char* force_gm = [] { const char* e = getenv("CC_GEMM_GM"); return (e && *e) ? e : (const char*)nullptr; }();
+    // Test switches, read at every launch: CC_GEMM_CFG = "b" / "m" / "h" / "s" forces the tile shape
+    // (256x256, 192x256, 256x128, 128x128), a second character "t" the staged loop; CC_GEMM_GM
+    // the band height of the tile order.
+    const char* force = getenv("CC_GEMM_CFG");
+    if (force && !*force) force = nullptr;
+    const char* force_gm = getenv("CC_GEMM_GM");
+    if (force_gm && !*force_gm) force_gm = nullptr;
     auto cost = [&](int bm, int bn, int per_cu, double eff) {
         const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn);
         const long slots = (long)n_cu * per_cu;

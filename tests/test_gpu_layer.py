@@ -266,7 +266,14 @@ def test_stage_attention_many_column_blocks_long_and_short_rows():
     ctx.close()
 
 
-def test_stage_projections_against_oracle_pieces():
+@pytest.mark.parametrize("tile", ["", "b", "m", "h", "s", "bt", "st"])
+def test_stage_projections_against_oracle_pieces(tile, monkeypatch):
+    """Every projection against the oracle's pieces, by default and with each GEMM tile shape
+    and K loop forced (the library reads CC_GEMM_CFG at every launch)."""
+    if tile:
+        monkeypatch.setenv("CC_GEMM_CFG", tile)
+    else:
+        monkeypatch.delenv("CC_GEMM_CFG", raising=False)
     model = ModelShape(512, 8, 2, 64, 768, 1e4, 1e-5, True, 1)
     N, M = 500, 203
     rng = np.random.default_rng(5)
