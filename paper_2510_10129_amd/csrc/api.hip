@@ -110,7 +110,7 @@ cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream) {
     memset(c->prof_ms, 0, sizeof(c->prof_ms));
     memset(c->prof_n, 0, sizeof(c->prof_n));
     c->rope = nullptr; c->xn = nullptr; c->q = nullptr; c->o = nullptr; c->y = nullptr;
-    c->mn = nullptr; c->act = nullptr; c->score = nullptr; c->n_sel = nullptr; c->flag = nullptr;
+    c->mn = nullptr; c->act = nullptr; c->attn_part = nullptr; c->score = nullptr; c->n_sel = nullptr; c->flag = nullptr;
     c->pinned = nullptr;
     const cc_model_desc& m = c->m;
     const size_t Mc = (size_t)m.M_cap, nq = (size_t)m.H_q * m.d_h;
@@ -125,6 +125,9 @@ cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream) {
     alloc((void**)&c->y, Mc * m.d * 4);
     alloc((void**)&c->mn, Mc * m.d * 2);
     alloc((void**)&c->act, Mc * m.f * 2);
+    // room for up to 8 key splits of the attention while the launch is small enough to want them
+    c->attn_part_rows = (int64_t)std::min<size_t>(Mc * m.H_q * 8, 196608);
+    alloc((void**)&c->attn_part, (size_t)c->attn_part_rows * (m.d_h + 4) * 4);
     alloc((void**)&c->score, (size_t)m.T_cap * 4);
     alloc((void**)&c->n_sel, 4);
     alloc((void**)&c->flag, 4);
@@ -151,7 +154,8 @@ cc_status cc_destroy(cc_ctx* c) {
     for (auto& p : c->used) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
     for (auto& p : c->pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
     (void)hipFree(c->rope); (void)hipFree(c->xn); (void)hipFree(c->q); (void)hipFree(c->o);
-    (void)hipFree(c->y); (void)hipFree(c->mn); (void)hipFree(c->act); (void)hipFree(c->score);
+    (void)hipFree(c->y); (void)hipFree(c->mn); (void)hipFree(c->act); (void)hipFree(c->attn_part);
+    (void)hipFree(c->score);
     (void)hipFree(c->n_sel); (void)hipFree(c->flag);
     if (c->pinned) (void)hipHostFree(c->pinned);
     delete c;
@@ -333,7 +337,7 @@ cc_status cc_step_sparse_attention(cc_ctx* c, const void* q, int32_t M, const in
     }
     {
         cc_prof_scope ps(c, CC_K_ATTN);
-        cc_launch_attention((const bf16_t*)q, M, idx, c->m, *kv, (bf16_t*)o, c->stream);
+        cc_launch_attention((const bf16_t*)q, M, idx, c->m, *kv, (bf16_t*)o, c->attn_part, c->attn_part_rows, c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;

@@ -40,6 +40,8 @@
 // first and last row of the tile.  Workgroups are issued longest-first and
 // workgroup id modulo H_kv picks the kv head, so the workgroups resident on
 // one XCD walk the same K/V stream through that XCD's L2.
+#include <stdlib.h>
+
 #include "cc_internal.h"
 #include <type_traits>
 
@@ -98,7 +100,7 @@ template <int D_H>
 __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     const bf16_t* __restrict__ q, int M, const int32_t* __restrict__ idx, int H_q, int H_kv,
     const bf16_t* __restrict__ Kc, const bf16_t* __restrict__ Vc, int64_t st, int64_t sh, int N,
-    bf16_t* __restrict__ o, int n_row_tiles, float scale_log2) {
+    bf16_t* __restrict__ o, int n_row_tiles, float scale_log2, int n_splits, float* __restrict__ part) {
     constexpr int KS = D_H / 16;          // k-steps of the QK^T contraction
     constexpr int DT = D_H / 32;          // 32-row tiles of O^T
     constexpr int CPRW = D_H / 8;         // 16-byte chunks per cache row
@@ -151,7 +153,22 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     const int limit = valid ? idx[mi] : -1;
     const int last_row = min(M - 1, (rt * 256 + 255) / g);
     const int kmax = idx[last_row];                    // rows are sorted: the block's longest span
-    const int n_tiles = kmax / BN_KEYS + 1;
+    // Key split: workgroup blockIdx.y of n_splits takes key tiles ta .. ta + n_tiles - 1 of the
+    // block's span and leaves unnormalised fp32 partial results for the merge kernel.
+    const int all_tiles = kmax / BN_KEYS + 1;
+    const int tiles_per = (all_tiles + n_splits - 1) / n_splits;
+    const int ta = blockIdx.y * tiles_per;
+    const int n_tiles = min(all_tiles - ta, tiles_per);
+    const int j_a = ta * BN_KEYS;                      // first key of this workgroup
+    const int64_t part_row = valid ? ((int64_t)blockIdx.y * M + mi) * H_q + kvh * g + hg : 0;
+    if (n_tiles <= 0) {                                // more splits than tiles: an empty part
+        if (valid && hf == 0) {
+            float* pm = part + part_row * (D_H + 4) + D_H;
+            pm[0] = -INFINITY;
+            pm[1] = 0.0f;
+        }
+        return;
+    }
 
     // wave-wide largest limit (tiles beyond it are skipped by this wave) and smallest
     // limit of a valid row (tiles that end at or below it need no mask)
@@ -376,7 +393,7 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
     //      but its newest tile after issuing K(t+4)).  Every wave passes 2 n_tiles + 3
     //      barriers; tiles past a wave's own last key only cost it the barriers and its loads.
     //      The scores of tile my_tiles (computed from whatever its stage holds) are never used.
-    const int my_tiles = wave_limit < 0 ? 0 : wave_limit / BN_KEYS + 1;
+    const int my_tiles = wave_limit < 0 ? 0 : max(0, min(wave_limit / BN_KEYS + 1 - ta, n_tiles));
     using yes = std::integral_constant<int, 1>;
     using no = std::integral_constant<int, 0>;
     int k_at = 0, v_at = 0;           // stages the address registers point at
@@ -393,8 +410,8 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
         }
     };
     if (grp == 0) {
-        dma_v(v_stage(0), 0);
-        if (n_tiles > 1) dma_v(v_stage(1), BN_KEYS);
+        dma_v(v_stage(0), j_a);
+        if (n_tiles > 1) dma_v(v_stage(1), j_a + BN_KEYS);
         phase_end(n_tiles > 1);                            // K(0), V(0) are in place
         if (my_tiles > 0) {                                // P0
             matrix_phase(no{});
@@ -402,20 +419,20 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
         }
         phase_end(n_tiles > 1);
         for (int t = 0; t < n_tiles; ++t) {
-            if (t < my_tiles) softmax(t * BN_KEYS);
+            if (t < my_tiles) softmax(j_a + t * BN_KEYS);
             phase_end(t + 1 < n_tiles);                    // V(t) has landed
             if (t < my_tiles) {
                 matrix_phase(yes{});
                 advance(true);
             }
-            if (t + 2 < n_tiles) dma_v(v_stage(t + 2), (t + 2) * BN_KEYS);
+            if (t + 2 < n_tiles) dma_v(v_stage(t + 2), j_a + (t + 2) * BN_KEYS);
             phase_end(true);
         }
         phase_end(false);
     } else {
-        dma_k(k_stage(0), 0);
-        if (n_tiles > 1) dma_k(k_stage(1), BN_KEYS);
-        if (n_tiles > 2) dma_k(k_stage(2), 2 * BN_KEYS);
+        dma_k(k_stage(0), j_a);
+        if (n_tiles > 1) dma_k(k_stage(1), j_a + BN_KEYS);
+        if (n_tiles > 2) dma_k(k_stage(2), j_a + 2 * BN_KEYS);
         if (n_tiles > 2) __builtin_amdgcn_s_waitcnt(((2 * NI) & 0xF) | (((2 * NI) >> 4) << 14) | (0x7 << 4) | (0xF << 8));
         phase_end(n_tiles > 1);                            // K(0), V(0) are in place
         phase_end(true);                                   // P0
@@ -425,20 +442,21 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
         }
         phase_end(n_tiles > 2);                            // K(1) has landed
         for (int t = 0; t < n_tiles; ++t) {
-            if (t < my_tiles) softmax(t * BN_KEYS);
+            if (t < my_tiles) softmax(j_a + t * BN_KEYS);
             phase_end(true);
             if (t < my_tiles) {
                 matrix_phase(yes{});
                 advance(true);
             }
-            if (t + 3 < n_tiles) dma_k(k_stage(t), (t + 3) * BN_KEYS);
+            if (t + 3 < n_tiles) dma_k(k_stage(t), j_a + (t + 3) * BN_KEYS);
             phase_end(t + 3 < n_tiles);                    // K(t+2) has landed
         }
     }
 
     // ---- normalise and write: lane holds 4 consecutive d per (dt, v/4) ----
     float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (valid) {
+    if (!valid) return;
+    if (n_splits == 1) {
         const float inv = 1.0f / l_tot;
         bf16_t* op = o + ((int64_t)mi * H_q + kvh * g + hg) * D_H;
 #pragma unroll
@@ -450,24 +468,102 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
                 for (int u = 0; u < 4; ++u) w[u] = (bf16_t)(acc_o[dt][vq * 4 + u] * inv);
                 *reinterpret_cast<bf16x4*>(op + dt * 32 + 8 * vq + 4 * hf) = w;
             }
+    } else {
+        // part row: d_h unnormalised sums, then the exponent's reference point and the row sum
+        float* pp = part + part_row * (D_H + 4);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                f32x4 w;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) w[u] = acc_o[dt][vq * 4 + u];
+                *reinterpret_cast<f32x4*>(pp + dt * 32 + 8 * vq + 4 * hf) = w;
+            }
+        if (hf == 0) {
+            pp[D_H] = m_run;
+            pp[D_H + 1] = l_tot;
+        }
     }
+}
+
+// Merge of a key-split launch: o = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s with m = max m_s.
+// One thread per (token, head) row and four output elements.
+template <int D_H>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, int64_t rows,
+                                                         int n_splits, bf16_t* __restrict__ o) {
+    constexpr int TPR = D_H / 4;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = t / TPR;
+    const int d0 = (int)(t % TPR) * 4;
+    if (row >= rows) return;
+    float m = -INFINITY;
+    for (int sp = 0; sp < n_splits; ++sp) m = fmaxf(m, part[(sp * rows + row) * (D_H + 4) + D_H]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.0f;
+    for (int sp = 0; sp < n_splits; ++sp) {
+        const float* pp = part + (sp * rows + row) * (D_H + 4);
+        const float ms = pp[D_H];
+        if (ms == -INFINITY) continue;                 // an empty part: its sums were never written
+        const float w = __builtin_amdgcn_exp2f(ms - m);
+        const f32x4 v = *reinterpret_cast<const f32x4*>(pp + d0);
+        acc += v * w;
+        l += pp[D_H + 1] * w;
+    }
+    const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+    bf16x4 w;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) w[u] = (bf16_t)(acc[u] * inv);
+    *reinterpret_cast<bf16x4*>(o + row * D_H + d0) = w;
 }
 
 }  // namespace
 
 void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_model_desc& m,
-                         const cc_kv_layer& kv, bf16_t* o, hipStream_t s) {
+                         const cc_kv_layer& kv, bf16_t* o, float* part, int64_t part_rows, hipStream_t s) {
     if (M <= 0) return;
     const int g = m.H_q / m.H_kv;
     const int n_row_tiles = (int)(((int64_t)M * g + 255) / 256);   // 256 (token, head) columns each
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)m.d_h);
-    dim3 grid(n_row_tiles * m.H_kv), block(512);
+    // A grid that does not fill the chip is split along the keys: S workgroups per block, each over
+    // 1/S of the block's key tiles, and a merge pass.  Model, in key-tile times: the longest
+    // workgroup (t_max / S tiles) or the whole work spread over the CUs, whichever is longer; the
+    // work is taken as half of blocks x t_max (spans grow with the position of the block's last
+    // token) with 30 % on top for the uneven end, as measured; plus the merge's traffic.
+    const int64_t rows = (int64_t)M * m.H_q;
+    const int n_wg = n_row_tiles * m.H_kv, n_cu = 256;
+    const int t_max = (kv.N + BN_KEYS - 1) / BN_KEYS;
+    int S = 1;
+    const char* force = getenv("CC_ATTN_SPLITS");     // test switch, read at every launch
+    if (force && *force) {
+        S = atoi(force);
+    } else if (part && n_wg < 2 * n_cu) {
+        const double tile_us = m.d_h == 128 ? 1.9 : 1.0;
+        const double spread = 1.3 * 0.5 * (double)n_wg * t_max / n_cu;
+        double best = t_max > spread ? t_max : spread;
+        for (int sp = 2; sp <= 8 && sp <= t_max; ++sp) {
+            if (sp * rows > part_rows) break;
+            const double longest = (double)((t_max + sp - 1) / sp);
+            const double merge_us = 3.0 + (double)(sp * rows) * (m.d_h + 4) * 4 / 4.0e6;
+            const double c = (longest > spread ? longest : spread) + merge_us / tile_us;
+            if (c < 0.95 * best) best = c, S = sp;
+        }
+    }
+    if (S < 1 || !part || S * rows > part_rows) S = 1;
+    if (S > t_max) S = t_max;
+    dim3 grid(n_row_tiles * m.H_kv, S), block(512);
     if (m.d_h == 128)
         hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, block, 0, s, q, M, idx, m.H_q, m.H_kv,
                            (const bf16_t*)kv.K, (const bf16_t*)kv.V, kv.stride_token, kv.stride_head,
-                           kv.N, o, n_row_tiles, scale_log2);
+                           kv.N, o, n_row_tiles, scale_log2, S, part);
     else
         hipLaunchKernelGGL(sparse_attn_kernel<64>, grid, block, 0, s, q, M, idx, m.H_q, m.H_kv,
                            (const bf16_t*)kv.K, (const bf16_t*)kv.V, kv.stride_token, kv.stride_head,
-                           kv.N, o, n_row_tiles, scale_log2);
+                           kv.N, o, n_row_tiles, scale_log2, S, part);
+    if (S > 1) {
+        const int64_t threads = rows * (m.d_h / 4);
+        dim3 mg((unsigned)((threads + 255) / 256));
+        if (m.d_h == 128) hipLaunchKernelGGL(attn_merge_kernel<128>, mg, dim3(256), 0, s, part, rows, S, o);
+        else hipLaunchKernelGGL(attn_merge_kernel<64>, mg, dim3(256), 0, s, part, rows, S, o);
+    }
 }

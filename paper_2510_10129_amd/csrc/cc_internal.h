@@ -35,6 +35,8 @@ struct cc_ctx {
     float* y;          // [M_cap][d]          residual stream after attention
     bf16_t* mn;        // [M_cap][d]          normalised MLP input
     bf16_t* act;       // [M_cap][f]          silu(gate)*up
+    float* attn_part;  // [attn_part_rows][d_h + 4]  partial results of a key-split attention launch
+    int64_t attn_part_rows;
     float* score;      // [T_cap]
     int32_t* n_sel;    // [1]
     int32_t* flag;     // [1] idx check result
@@ -103,8 +105,9 @@ void cc_launch_rmsnorm_f32(const float* y, int M, int d, const bf16_t* w, float 
 void cc_launch_qkv(const bf16_t* xn, int M, const int32_t* idx, const bf16_t* w_qkv,
                    const bf16_t* b_qkv, const cc_model_desc& m, const float2* rope,
                    const cc_kv_layer& kv, bf16_t* q_out, hipStream_t s);
+// `part` ([part_rows][d_h + 4] fp32, may be NULL) lets a launch with few workgroups split the keys.
 void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_model_desc& m,
-                         const cc_kv_layer& kv, bf16_t* o, hipStream_t s);
+                         const cc_kv_layer& kv, bf16_t* o, float* part, int64_t part_rows, hipStream_t s);
 void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hidden,
                      const int32_t* gather_idx, const cc_model_desc& m, float* y, hipStream_t s);
 void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16_t* w_up,

@@ -186,9 +186,16 @@ def test_idx_check_and_argument_errors():
 
 
 # ------------------------------------------------------------ single stages
-def test_stage_attention_peaked_random():
+@pytest.mark.parametrize("splits", ["", "1", "2", "3", "8"])
+def test_stage_attention_peaked_random(splits, monkeypatch):
     """The attention kernel alone, on q/K/V drawn directly so that the softmax is
-    sharply peaked and the causal boundary matters."""
+    sharply peaked and the causal boundary matters; with the launcher's own choice of key
+    splits and with 1, 2, 3 and 8 forced (the library reads CC_ATTN_SPLITS at every launch;
+    more splits than key tiles leave empty parts)."""
+    if splits:
+        monkeypatch.setenv("CC_ATTN_SPLITS", splits)
+    else:
+        monkeypatch.delenv("CC_ATTN_SPLITS", raising=False)
     for (H_q, H_kv, d_h, N, seed) in ((8, 2, 128, 700, 0), (4, 4, 64, 333, 1), (7, 1, 128, 190, 2),
                                       (16, 2, 64, 1000, 3)):
         rng = np.random.default_rng(seed)
