@@ -110,7 +110,7 @@ cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream) {
     memset(c->prof_ms, 0, sizeof(c->prof_ms));
     memset(c->prof_n, 0, sizeof(c->prof_n));
     c->rope = nullptr; c->xn = nullptr; c->q = nullptr; c->o = nullptr; c->y = nullptr;
-    c->mn = nullptr; c->act = nullptr; c->attn_part = nullptr; c->score = nullptr; c->n_sel = nullptr; c->flag = nullptr;
+    c->mn = nullptr; c->act = nullptr; c->attn_part = nullptr; c->gemm_part = nullptr; c->score = nullptr; c->n_sel = nullptr; c->flag = nullptr;
     c->pinned = nullptr;
     const cc_model_desc& m = c->m;
     const size_t Mc = (size_t)m.M_cap, nq = (size_t)m.H_q * m.d_h;
@@ -128,6 +128,12 @@ cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream) {
     // room for up to 8 key splits of the attention while the launch is small enough to want them
     c->attn_part_rows = (int64_t)std::min<size_t>(Mc * m.H_q * 8, 196608);
     alloc((void**)&c->attn_part, (size_t)c->attn_part_rows * (m.d_h + 4) * 4);
+    // shares of a split-K projection: up to 8 x [M_cap][widest padded output], at most 128 MB
+    {
+        const size_t widest = std::max<size_t>(std::max<size_t>((size_t)m.d, nq + 2 * (size_t)m.H_kv * m.d_h), 2 * (size_t)m.f);
+        c->gemm_part_floats = (int64_t)std::min<size_t>(8 * Mc * ((widest + 255) / 256 * 256), (size_t)32 << 20);
+    }
+    alloc((void**)&c->gemm_part, (size_t)c->gemm_part_floats * 4);
     alloc((void**)&c->score, (size_t)m.T_cap * 4);
     alloc((void**)&c->n_sel, 4);
     alloc((void**)&c->flag, 4);
@@ -154,7 +160,7 @@ cc_status cc_destroy(cc_ctx* c) {
     for (auto& p : c->used) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
     for (auto& p : c->pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
     (void)hipFree(c->rope); (void)hipFree(c->xn); (void)hipFree(c->q); (void)hipFree(c->o);
-    (void)hipFree(c->y); (void)hipFree(c->mn); (void)hipFree(c->act); (void)hipFree(c->attn_part);
+    (void)hipFree(c->y); (void)hipFree(c->mn); (void)hipFree(c->act); (void)hipFree(c->attn_part); (void)hipFree(c->gemm_part);
     (void)hipFree(c->score);
     (void)hipFree(c->n_sel); (void)hipFree(c->flag);
     if (c->pinned) (void)hipHostFree(c->pinned);
@@ -317,7 +323,7 @@ cc_status cc_step_qkv_rope_scatter(cc_ctx* c, const void* xn, int32_t M, const i
     {
         cc_prof_scope ps(c, CC_K_QKV);
         cc_launch_qkv((const bf16_t*)xn, M, idx, (const bf16_t*)w_qkv, (const bf16_t*)b_qkv, c->m,
-                      c->rope, *kv, (bf16_t*)q_out, c->stream);
+                      c->rope, *kv, (bf16_t*)q_out, c->gemm_part, c->gemm_part_floats, c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;
@@ -353,7 +359,7 @@ cc_status cc_step_oproj_residual(cc_ctx* c, const void* o, int32_t M, const void
     {
         cc_prof_scope ps(c, CC_K_OPROJ);
         cc_launch_oproj((const bf16_t*)o, M, (const bf16_t*)w_o, (const bf16_t*)hidden, gather_idx,
-                        c->m, y, c->stream);
+                        c->m, y, c->gemm_part, c->gemm_part_floats, c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;
@@ -375,11 +381,13 @@ cc_status cc_step_mlp(cc_ctx* c, const float* y, int32_t M, const void* w_post_n
     }
     {
         cc_prof_scope ps(c, CC_K_GATE_UP);
-        cc_launch_gate_up(c->mn, M, (const bf16_t*)w_gate, (const bf16_t*)w_up, c->m, c->act, c->stream);
+        cc_launch_gate_up(c->mn, M, (const bf16_t*)w_gate, (const bf16_t*)w_up, c->m, c->act, c->gemm_part,
+                          c->gemm_part_floats, c->stream);
     }
     {
         cc_prof_scope ps(c, CC_K_DOWN);
-        cc_launch_down(c->act, M, (const bf16_t*)w_down, y, c->m, (bf16_t*)out, c->stream);
+        cc_launch_down(c->act, M, (const bf16_t*)w_down, y, c->m, (bf16_t*)out, c->gemm_part, c->gemm_part_floats,
+                       c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;

@@ -199,6 +199,46 @@ struct EpiDown {
     }
 };
 
+// Split-K: workgroup row blockIdx.y of a launch computes the products over its share of K and
+// leaves its fp32 tile in a workspace [split][row][padded column]; splitk_finish_kernel adds the
+// shares and applies the launch's own epilogue functor.
+struct EpiPartial {
+    float* ws;
+    int64_t ld, split_stride;
+    template <int BN>
+    __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow, int swz) const {
+        float* dst = ws + blockIdx.y * split_stride + (int64_t)m * ld + bn * BN + cc;
+        const f32x4* cr = reinterpret_cast<const f32x4*>(crow + (cc ^ swz));
+        reinterpret_cast<f32x4*>(dst)[0] = cr[0];
+        reinterpret_cast<f32x4*>(dst)[1] = cr[1];
+    }
+};
+
+// One workgroup per 8 rows of one 256-column tile: sums the shares of each 8-column chunk into an
+// LDS row, then every thread calls the functor on its chunk (functors may read other chunks of
+// the row: the RoPE partner, the up half of a gate/up tile).
+template <class Epi>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ ws, int64_t ld,
+                                                            int64_t split_stride, int n_splits, int M, Epi epi) {
+    constexpr int BN = 256, TPR = BN / 8, ROWS = 256 / TPR;
+    __shared__ __align__(16) float stage[ROWS][BN];
+    const int r = threadIdx.x / TPR, cc = (threadIdx.x % TPR) * 8;
+    const int bn = blockIdx.x, m = blockIdx.y * ROWS + r;
+    if (m < M) {
+        const float* src = ws + (int64_t)m * ld + bn * BN + cc;
+        f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < n_splits; ++sp) {
+            const f32x4* p = reinterpret_cast<const f32x4*>(src + sp * split_stride);
+            a += p[0];
+            b += p[1];
+        }
+        *reinterpret_cast<f32x4*>(&stage[r][cc]) = a;
+        *reinterpret_cast<f32x4*>(&stage[r][cc + 4]) = b;
+    }
+    __syncthreads();
+    if (m < M) epi.template operator()<BN>(m, bn, cc, stage[r], 0);
+}
+
 // Consecutive workgroup ids go round-robin to the 8 XCDs (each with its own
 // L2).  Every XCD gets one contiguous range of the tile sequence, and the
 // sequence walks bands of GM row-tiles column by column, so the workgroups that
@@ -565,8 +605,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
         r = r < left ? r : left - 1;
         bo[i] = (uint32_t)((r * bsrc.ldb + c * 8) * 2);
     }
-    const char* abase = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
-    const char* bbase = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, hi_half ? 1 : 0));
+    // K is this launch's share per workgroup row: row blockIdx.y starts blockIdx.y * K columns in
+    const int64_t kz = (int64_t)blockIdx.y * K * 2;
+    const char* abase = reinterpret_cast<const char*>(A + (int64_t)m0 * lda) + kz;
+    const char* bbase = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, hi_half ? 1 : 0)) + kz;
     const int wbase = wave_u * DPS * 16 * BKS;
     auto scalar_ptr = [](const char* p) -> const char* {   // keeps the base in scalar registers
         const uint64_t u = reinterpret_cast<uint64_t>(p);
@@ -702,7 +744,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
 // cost.
 template <class BSrc, class Epi>
 void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int ldb, int gm_big,
-                 BSrc bsrc, Epi epi, hipStream_t s) {
+                 BSrc bsrc, Epi epi, float* ws, int64_t ws_floats, hipStream_t s) {
     static const int n_cu = [] {
         int dev = 0, n = 256;
         if (hipGetDevice(&dev) == hipSuccess)
@@ -711,16 +753,20 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     }();
     // Test switches, read at every launch: CC_GEMM_CFG = "b" / "m" / "h" / "s" forces the tile shape
     // (256x256, 192x256, 256x128, 128x128), a second character "t" the staged loop; CC_GEMM_GM
-    // the band height of the tile order.
+    // the band height of the tile order; CC_GEMM_SPLITK the number of K shares (1 = none).
     const char* force = getenv("CC_GEMM_CFG");
     if (force && !*force) force = nullptr;
     const char* force_gm = getenv("CC_GEMM_GM");
     if (force_gm && !*force_gm) force_gm = nullptr;
-    auto cost = [&](int bm, int bn, int per_cu, double eff) {
-        const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn);
+    const char* force_sk = getenv("CC_GEMM_SPLITK");
+    if (force_sk && !*force_sk) force_sk = nullptr;
+    auto rounds_of = [&](int bm, int bn, int per_cu, int shares) {
+        const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn) * shares;
         const long slots = (long)n_cu * per_cu;
-        const long rounds = (tiles + slots - 1) / slots;
-        return (double)rounds * per_cu * bm * bn / eff;
+        return (tiles + slots - 1) / slots;
+    };
+    auto cost = [&](int bm, int bn, int per_cu, double eff) {
+        return (double)rounds_of(bm, bn, per_cu, 1) * per_cu * bm * bn / eff;
     };
     // ring loop: whole groups of NS slices, 32-bit lane offsets within a tile's rows
     bool ring = K % (BKS * NS) == 0 && (int64_t)lda * 256 * 2 < (1ll << 31) &&
@@ -733,25 +779,63 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     if (ring && ch < best) pick = 'h', best = ch;               // these two have no staged variant
     if (ring && cm < best) pick = 'm', best = cm;
     if (force && (force[0] == 'b' || force[0] == 's' || ((force[0] == 'h' || force[0] == 'm') && ring))) pick = force[0];
+    // Split-K for grids that leave most CUs idle (few rows, long K): S workgroup rows, each over K/S
+    // columns, with the 256-wide tiles, at most one round of workgroups, and a finishing pass.
+    // Times in microseconds: 0.8 per 32-column slice of a 256x256 tile, 6 per round for the ends of
+    // a tile, the finishing pass at 4 TB/s.
+    int S = 1;
+    if (ring && ws) {
+        const double slice_us = 0.8 * K / BKS / 65536.0;        // per unit of tile area
+        const double n_pad = (double)((N_tiles_cols + 255) / 256) * 256;
+        auto split_ok = [&](int bm, int sp, int k_min) {
+            return (K / (BKS * NS)) % sp == 0 && K / sp >= k_min && rounds_of(bm, 256, 1, sp) == 1 &&
+                   (double)sp * M * n_pad <= (double)ws_floats;
+        };
+        if (force_sk) {
+            const int sp = atoi(force_sk);
+            const int bm = pick == 'm' ? 192 : 256;
+            if (sp > 1 && sp <= 16 && split_ok(bm, sp, BKS * NS)) S = sp, pick = bm == 192 ? 'm' : 'b';
+        } else if (!force) {
+            double t_best = best * slice_us + 6.0 * rounds_of(pick == 's' ? 128 : pick == 'm' ? 192 : 256,
+                                                               (pick == 'b' || pick == 'm') ? 256 : 128,
+                                                               pick == 's' ? 2 : 1, 1);
+            const double t_unsplit = t_best;
+            for (int bm = 256; bm >= 192; bm -= 64) {
+                const double eff = bm == 256 ? 1.0 : 0.8;
+                for (int sp = 2; sp <= 16; ++sp) {
+                    if (!split_ok(bm, sp, 512)) continue;
+                    const double t = bm * 256.0 / eff / sp * slice_us + 6.0 + 4.0 + sp * M * n_pad * 4 / 4.0e6;
+                    if (t < t_best && t < 0.9 * t_unsplit) t_best = t, S = sp, pick = bm == 256 ? 'b' : 'm';
+                }
+            }
+        }
+    }
     const int bm = pick == 's' ? 128 : pick == 'm' ? 192 : 256, bn = (pick == 'b' || pick == 'm') ? 256 : 128;
     const int tiles_m = (M + bm - 1) / bm, tiles_n = (N_tiles_cols + bn - 1) / bn;
     int GM = pick == 's' ? 2 * gm_big : gm_big;
     if (force_gm) GM = atoi(force_gm);
     GM = GM < 1 ? 1 : (GM > tiles_m ? tiles_m : GM);
-    const dim3 grid(tiles_m * tiles_n);
-#define CC_LAUNCH(KERN, BM_, BN_, WM_, WN_)                                                        \
-    hipLaunchKernelGGL((KERN<BM_, BN_, WM_, WN_, BSrc, Epi>), grid, dim3(WM_ * WN_ * 64), 0, s, A, \
-                       lda, M, K, tiles_m, tiles_n, GM, bsrc, epi)
-    if (pick == 'b') {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4);
-        else CC_LAUNCH(gemm_nt_kernel, 256, 256, 2, 4);
+    const dim3 grid(tiles_m * tiles_n, S);
+#define CC_LAUNCH(KERN, BM_, BN_, WM_, WN_, EPI_T, EPI_V, K_)                                        \
+    hipLaunchKernelGGL((KERN<BM_, BN_, WM_, WN_, BSrc, EPI_T>), grid, dim3(WM_ * WN_ * 64), 0, s, A, \
+                       lda, M, K_, tiles_m, tiles_n, GM, bsrc, EPI_V)
+    if (S > 1) {
+        const int64_t ld = (int64_t)tiles_n * 256;
+        EpiPartial pe{ws, ld, (int64_t)M * ld};
+        if (pick == 'b') CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, EpiPartial, pe, K / S);
+        else CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, EpiPartial, pe, K / S);
+        hipLaunchKernelGGL((splitk_finish_kernel<Epi>), dim3(tiles_n, (M + 7) / 8), dim3(256), 0, s, ws, ld,
+                           (int64_t)M * ld, S, M, epi);
+    } else if (pick == 'b') {
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K);
+        else CC_LAUNCH(gemm_nt_kernel, 256, 256, 2, 4, Epi, epi, K);
     } else if (pick == 'm') {
-        CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4);
+        CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K);
     } else if (pick == 'h') {
-        CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2);
+        CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2, Epi, epi, K);
     } else {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 128, 2, 2);
-        else CC_LAUNCH(gemm_nt_kernel, 128, 128, 2, 2);
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 128, 2, 2, Epi, epi, K);
+        else CC_LAUNCH(gemm_nt_kernel, 128, 128, 2, 2, Epi, epi, K);
     }
 #undef CC_LAUNCH
 }
@@ -760,37 +844,38 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
 
 void cc_launch_qkv(const bf16_t* xn, int M, const int32_t* idx, const bf16_t* w_qkv,
                    const bf16_t* b_qkv, const cc_model_desc& m, const float2* rope,
-                   const cc_kv_layer& kv, bf16_t* q_out, hipStream_t s) {
+                   const cc_kv_layer& kv, bf16_t* q_out, float* ws, int64_t ws_floats, hipStream_t s) {
     if (M <= 0) return;
     const int N = (m.H_q + 2 * m.H_kv) * m.d_h;
     BSingle b{w_qkv, m.d, N};
     EpiQKV e{idx, b_qkv, rope, m.H_q, m.H_kv, m.d_h, N, q_out,
              (bf16_t*)kv.K, (bf16_t*)kv.V, kv.stride_token, kv.stride_head};
-    launch_gemm(xn, m.d, M, N, m.d, m.d, 4, b, e, s);
+    launch_gemm(xn, m.d, M, N, m.d, m.d, 4, b, e, ws, ws_floats, s);
 }
 
 void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hidden,
-                     const int32_t* gather_idx, const cc_model_desc& m, float* y, hipStream_t s) {
+                     const int32_t* gather_idx, const cc_model_desc& m, float* y, float* ws,
+                     int64_t ws_floats, hipStream_t s) {
     if (M <= 0) return;
     const int K = m.H_q * m.d_h;
     BSingle b{w_o, K, m.d};
     EpiOProj e{hidden, gather_idx, m.d, y};
-    launch_gemm(o, K, M, m.d, K, K, 4, b, e, s);
+    launch_gemm(o, K, M, m.d, K, K, 4, b, e, ws, ws_floats, s);
 }
 
 void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16_t* w_up,
-                       const cc_model_desc& m, bf16_t* act, hipStream_t s) {
+                       const cc_model_desc& m, bf16_t* act, float* ws, int64_t ws_floats, hipStream_t s) {
     if (M <= 0) return;
     BDual b{w_gate, w_up, m.d, m.f};
     EpiGateUp e{m.f, act};
     // each 128-column tile holds 64 gate + 64 up columns: 2*f tile columns in total
-    launch_gemm(mn, m.d, M, 2 * m.f, m.d, m.d, 4, b, e, s);
+    launch_gemm(mn, m.d, M, 2 * m.f, m.d, m.d, 4, b, e, ws, ws_floats, s);
 }
 
 void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float* y,
-                    const cc_model_desc& m, bf16_t* out, hipStream_t s) {
+                    const cc_model_desc& m, bf16_t* out, float* ws, int64_t ws_floats, hipStream_t s) {
     if (M <= 0) return;
     BSingle b{w_down, m.f, m.d};
     EpiDown e{y, m.d, out};
-    launch_gemm(act, m.f, M, m.d, m.f, m.f, 8, b, e, s);
+    launch_gemm(act, m.f, M, m.d, m.f, m.f, 8, b, e, ws, ws_floats, s);
 }

@@ -273,14 +273,17 @@ def test_stage_attention_many_column_blocks_long_and_short_rows():
     ctx.close()
 
 
-@pytest.mark.parametrize("tile", ["", "b", "m", "h", "s", "bt", "st"])
-def test_stage_projections_against_oracle_pieces(tile, monkeypatch):
-    """Every projection against the oracle's pieces, by default and with each GEMM tile shape
-    and K loop forced (the library reads CC_GEMM_CFG at every launch)."""
-    if tile:
-        monkeypatch.setenv("CC_GEMM_CFG", tile)
-    else:
-        monkeypatch.delenv("CC_GEMM_CFG", raising=False)
+@pytest.mark.parametrize("tile,splitk", [("", ""), ("b", ""), ("m", ""), ("h", ""), ("s", ""), ("bt", ""), ("st", ""),
+                                         ("", "2"), ("", "3"), ("", "4"), ("m", "2")])
+def test_stage_projections_against_oracle_pieces(tile, splitk, monkeypatch):
+    """Every projection against the oracle's pieces, by default, with each GEMM tile shape and K
+    loop forced, and with 2, 3 and 4 shares of K (3 divides only the down projection's K here, 4
+    leaves a share of exactly one ring of slices); the library reads the switches at every launch."""
+    for name, val in (("CC_GEMM_CFG", tile), ("CC_GEMM_SPLITK", splitk)):
+        if val:
+            monkeypatch.setenv(name, val)
+        else:
+            monkeypatch.delenv(name, raising=False)
     model = ModelShape(512, 8, 2, 64, 768, 1e4, 1e-5, True, 1)
     N, M = 500, 203
     rng = np.random.default_rng(5)
