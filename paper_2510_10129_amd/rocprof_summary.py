@@ -18,6 +18,8 @@ import re
 import sys
 
 KINDS = (
+    # the pieces of split launches first: their names also contain an epilogue's or a kernel's name
+    ("splitk_finish_kernel", "splitk_finish"), ("EpiPartial", "splitk_share"), ("attn_merge_kernel", "attn_merge"),
     ("EpiGateUp", "gate_up"), ("EpiDown", "down"), ("EpiQKV", "qkv"), ("EpiOProj", "oproj"),
     ("sparse_attn_kernel", "attn"), ("gather_rmsnorm_kernel", "gather_norm"),
     ("rmsnorm_f32_kernel", "post_norm"), ("colsum_kernel", "colsum"), ("select_kernel", "select"),
