@@ -120,6 +120,31 @@ def test_shapes_and_edge_cases(model, N, kind):
     _assert_layer(got, ref, Ks, Vs, idx, f"{kind} d={model.d} g={model.g} d_h={model.d_h}", kv_scale=3.0)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_small_layers(seed):
+    """Seeded random layer shapes and token sets (head dims, group sizes 1..8, widths that take the
+    ring and the staged K loop, context lengths across several key tiles, sparse and dense idx):
+    the whole layer against the oracle with the launchers' own choices."""
+    rng = np.random.default_rng(1000 + seed)
+    d_h = int(rng.choice([64, 128]))
+    H_kv = int(rng.choice([1, 2, 4]))
+    g = int(rng.choice([1, 2, 3, 4, 7, 8]))
+    d = 64 * int(rng.integers(2, 17))
+    f = 64 * int(rng.integers(1, 17))
+    model = ModelShape(d, g * H_kv, H_kv, d_h, f, float(rng.choice([1e4, 5e5, 1e6])),
+                       float(rng.choice([1e-5, 1e-6])), bool(rng.integers(0, 2)), 1)
+    N = int(rng.integers(20, 1200))
+    marks = rng.random(N) < rng.uniform(0.05, 0.9)
+    marks[N - 1] = True
+    idx = np.nonzero(marks)[0]
+    w = gen.layer_weights(model, 0, seed=2000 + seed)
+    xl, xg = _x_bits(N, d, 3 * seed + 1), _x_bits(N, d, 3 * seed + 2)
+    Ks, Vs = fixture.stale_cache_one_layer(xl, w, model)
+    rows = None if len(idx) <= 96 else np.unique(np.concatenate([[0, len(idx) - 1], rng.choice(len(idx), 64, replace=False)]))
+    got, ref = _run_layer(model, xg, idx, Ks, Vs, idx, w, rows=rows)
+    _assert_layer(got, ref, Ks, Vs, idx, f"seed {seed}: d={d} f={f} {g * H_kv}q/{H_kv}kv d_h={d_h} N={N} M={len(idx)}")
+
+
 def test_compact_hidden_and_zero_rows():
     model = SHAPES[0][0]
     N = 150
