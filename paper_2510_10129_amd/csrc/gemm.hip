@@ -200,35 +200,52 @@ struct EpiDown {
 };
 
 // Split-K: workgroup row blockIdx.y of a launch computes the products over its share of K and
-// leaves its fp32 tile in a workspace [split][row][padded column]; splitk_finish_kernel adds the
-// shares and applies the launch's own epilogue functor.
+// leaves its fp32 tile in a workspace [share][tile slot][256][256] (slot = the tile's index
+// within the launch); splitk_finish_kernel adds the shares and applies the launch's own
+// epilogue functor.
 struct EpiPartial {
     float* ws;
-    int64_t ld, split_stride;
+    int64_t share_stride;     // floats per share: slots * 65536
+    int slot, m0;             // set by the kernel: this workgroup's slot and first row
     template <int BN>
     __device__ __forceinline__ void operator()(int m, int bn, int cc, const float* crow, int swz) const {
-        float* dst = ws + blockIdx.y * split_stride + (int64_t)m * ld + bn * BN + cc;
+        static_assert(BN == 256, "slots are 256 columns wide");
+        float* dst = ws + blockIdx.y * share_stride + (int64_t)slot * 65536 + (m - m0) * 256 + cc;
         const f32x4* cr = reinterpret_cast<const f32x4*>(crow + (cc ^ swz));
         reinterpret_cast<f32x4*>(dst)[0] = cr[0];
         reinterpret_cast<f32x4*>(dst)[1] = cr[1];
     }
 };
-
-// One workgroup per 8 rows of one 256-column tile: sums the shares of each 8-column chunk into an
-// LDS row, then every thread calls the functor on its chunk (functors may read other chunks of
-// the row: the RoPE partner, the up half of a gate/up tile).
 template <class Epi>
-__global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ ws, int64_t ld,
-                                                            int64_t split_stride, int n_splits, int M, Epi epi) {
+__device__ __forceinline__ Epi epi_for_tile(const Epi& e, int, int) { return e; }
+__device__ __forceinline__ EpiPartial epi_for_tile(const EpiPartial& e, int slot, int m0) {
+    EpiPartial r = e;
+    r.slot = slot;
+    r.m0 = m0;
+    return r;
+}
+
+__device__ __forceinline__ void tile_of_seq(int vb, int tiles_m, int tiles_n, int GM, int* bm, int* bn);
+
+// One workgroup per 8 rows of one tile slot: sums the shares of each 8-column chunk into an LDS
+// row, then every thread calls the functor on its chunk (functors may read other chunks of the
+// row: the RoPE partner, the up half of a gate/up tile).
+template <class Epi>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ ws, int64_t share_stride,
+                                                            int n_shares, int M, int BM, int vb0, int tiles_m,
+                                                            int tiles_n, int GM, Epi epi) {
     constexpr int BN = 256, TPR = BN / 8, ROWS = 256 / TPR;
     __shared__ __align__(16) float stage[ROWS][BN];
     const int r = threadIdx.x / TPR, cc = (threadIdx.x % TPR) * 8;
-    const int bn = blockIdx.x, m = blockIdx.y * ROWS + r;
-    if (m < M) {
-        const float* src = ws + (int64_t)m * ld + bn * BN + cc;
+    int bm, bn;
+    tile_of_seq(vb0 + blockIdx.x, tiles_m, tiles_n, GM, &bm, &bn);
+    const int row = blockIdx.y * ROWS + r, m = bm * BM + row;
+    const bool on = row < BM && m < M;
+    if (on) {
+        const float* src = ws + (int64_t)blockIdx.x * 65536 + row * 256 + cc;
         f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
-        for (int sp = 0; sp < n_splits; ++sp) {
-            const f32x4* p = reinterpret_cast<const f32x4*>(src + sp * split_stride);
+        for (int sp = 0; sp < n_shares; ++sp) {
+            const f32x4* p = reinterpret_cast<const f32x4*>(src + sp * share_stride);
             a += p[0];
             b += p[1];
         }
@@ -236,7 +253,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
         *reinterpret_cast<f32x4*>(&stage[r][cc + 4]) = b;
     }
     __syncthreads();
-    if (m < M) epi.template operator()<BN>(m, bn, cc, stage[r], 0);
+    if (on) epi.template operator()<BN>(m, bn, cc, stage[r], 0);
 }
 
 // Consecutive workgroup ids go round-robin to the 8 XCDs (each with its own
@@ -244,17 +261,26 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
 // sequence walks bands of GM row-tiles column by column, so the workgroups that
 // run together on an XCD form a GM x (32/GM) block of tiles: they share GM
 // tiles of A and 32/GM tiles of B through that L2.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int GM, int* bm,
-                                              int* bn) {
-    const int nb = tiles_m * tiles_n;
-    const int q = nb >> 3, r = nb & 7;
-    const int x = bid & 7, local = bid >> 3;
-    const int vb = x * q + (x < r ? x : r) + local;
+// tile `vb` of the sequence (bands of GM row-tiles, column by column)
+__device__ __forceinline__ void tile_of_seq(int vb, int tiles_m, int tiles_n, int GM, int* bm, int* bn) {
     const int band = GM * tiles_n;
     const int b = vb / band, rb = vb - b * band;
     const int gm = min(GM, tiles_m - b * GM);
     *bm = b * GM + rb % gm;
     *bn = rb / gm;
+}
+// workgroup `bid` of a launch over tiles vb0 .. vb0 + nb - 1 of the sequence; returns its tile's index
+__device__ __forceinline__ int tile_of_block(int bid, int nb, int vb0, int tiles_m, int tiles_n, int GM,
+                                             int* bm, int* bn) {
+    const int q = nb >> 3, r = nb & 7;
+    const int x = bid & 7, local = bid >> 3;
+    const int vb = vb0 + x * q + (x < r ? x : r) + local;
+    tile_of_seq(vb, tiles_m, tiles_n, GM, bm, bn);
+    return vb;
+}
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int GM, int* bm,
+                                              int* bn) {
+    (void)tile_of_block(bid, tiles_m * tiles_n, 0, tiles_m, tiles_n, GM, bm, bn);
 }
 
 // 16 bytes per lane straight from global memory into LDS (no VGPR staging, no
@@ -538,8 +564,8 @@ constexpr int NS = 4;     // ring slots
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
-    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int GM, BSrc bsrc,
-    Epi epi) {
+    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int GM, int nb, int vb0,
+    BSrc bsrc, Epi epi) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -569,7 +595,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
     int bm, bn;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, GM, &bm, &bn);
+    const int vb = tile_of_block(blockIdx.x, nb, vb0, tiles_m, tiles_n, GM, &bm, &bn);   // this launch covers tiles vb0 .. vb0 + nb - 1
     const int m0 = bm * BM;
 
     // One DMA instruction moves 16 slice rows (16 x 64 B).  Lane L fills physical
@@ -732,7 +758,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
     __syncthreads();   // every wave has finished reading the ring
     store_tile_ring<BM, BN, WAVES_M, WAVES_N, RG>(acc, reinterpret_cast<float*>(sl0), reinterpret_cast<float*>(sl1),
                                               reinterpret_cast<float*>(sl2), reinterpret_cast<float*>(sl3),
-                                              m0, bn, M, epi);
+                                              m0, bn, M, epi_for_tile(epi, vb - vb0, m0));
 }
 
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
@@ -779,17 +805,23 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     if (ring && ch < best) pick = 'h', best = ch;               // these two have no staged variant
     if (ring && cm < best) pick = 'm', best = cm;
     if (force && (force[0] == 'b' || force[0] == 's' || ((force[0] == 'h' || force[0] == 'm') && ring))) pick = force[0];
-    // Split-K for grids that leave most CUs idle (few rows, long K): S workgroup rows, each over K/S
-    // columns, with the 256-wide tiles, at most one round of workgroups, and a finishing pass.
-    // Times in microseconds: 0.8 per 32-column slice of a 256x256 tile, 6 per round for the ends of
-    // a tile, the finishing pass at 4 TB/s.
+    // Split-K for the part of a grid that leaves most CUs idle: the tiles of a last round that
+    // fills at most half the chip (all tiles, if there is no full round) are computed by S
+    // workgroup rows, each over K/S columns, with S x tiles <= CUs, and a finishing pass; the full
+    // rounds before them run as a launch of their own.  256-wide tiles only.  Times in
+    // microseconds: 0.8 per 32-column slice of a 256x256 tile, 6 per round for the ends of a tile,
+    // the finishing pass at 4 TB/s.
     int S = 1;
     if (ring && ws) {
         const double slice_us = 0.8 * K / BKS / 65536.0;        // per unit of tile area
-        const double n_pad = (double)((N_tiles_cols + 255) / 256) * 256;
+        auto rem_of = [&](int bm) {
+            const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + 255) / 256);
+            return (int)(tiles % n_cu == 0 && tiles > 0 ? n_cu : tiles % n_cu);
+        };
         auto split_ok = [&](int bm, int sp, int k_min) {
-            return (K / (BKS * NS)) % sp == 0 && K / sp >= k_min && rounds_of(bm, 256, 1, sp) == 1 &&
-                   (double)sp * M * n_pad <= (double)ws_floats;
+            const int rem = rem_of(bm);
+            return (K / (BKS * NS)) % sp == 0 && K / sp >= k_min && (long)rem * sp <= n_cu &&
+                   (double)sp * rem * 65536.0 <= (double)ws_floats;
         };
         if (force_sk) {
             const int sp = atoi(force_sk);
@@ -801,10 +833,13 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
                                                                pick == 's' ? 2 : 1, 1);
             const double t_unsplit = t_best;
             for (int bm = 256; bm >= 192; bm -= 64) {
-                const double eff = bm == 256 ? 1.0 : 0.8;
+                const double tile_us = bm * 256.0 / (bm == 256 ? 1.0 : 0.8) * slice_us;
+                const long full_rounds = rounds_of(bm, 256, 1, 1) - 1;
+                const int rem = rem_of(bm);
                 for (int sp = 2; sp <= 16; ++sp) {
                     if (!split_ok(bm, sp, 512)) continue;
-                    const double t = bm * 256.0 / eff / sp * slice_us + 6.0 + 4.0 + sp * M * n_pad * 4 / 4.0e6;
+                    const double t = full_rounds * (tile_us + 6.0) + tile_us / sp + 6.0 + 4.0 +
+                                     (double)sp * rem * 65536.0 * 4 / 4.0e6;
                     if (t < t_best && t < 0.9 * t_unsplit) t_best = t, S = sp, pick = bm == 256 ? 'b' : 'm';
                 }
             }
@@ -815,29 +850,38 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     int GM = pick == 's' ? 2 * gm_big : gm_big;
     if (force_gm) GM = atoi(force_gm);
     GM = GM < 1 ? 1 : (GM > tiles_m ? tiles_m : GM);
-    const dim3 grid(tiles_m * tiles_n, S);
-#define CC_LAUNCH(KERN, BM_, BN_, WM_, WN_, EPI_T, EPI_V, K_)                                        \
-    hipLaunchKernelGGL((KERN<BM_, BN_, WM_, WN_, BSrc, EPI_T>), grid, dim3(WM_ * WN_ * 64), 0, s, A, \
-                       lda, M, K_, tiles_m, tiles_n, GM, bsrc, EPI_V)
+    const int n_tiles = tiles_m * tiles_n;
+#define CC_LAUNCH(KERN, BM_, BN_, WM_, WN_, EPI_T, EPI_V, K_, NB_, VB0_, GY_)                              \
+    hipLaunchKernelGGL((KERN<BM_, BN_, WM_, WN_, BSrc, EPI_T>), dim3(NB_, GY_), dim3(WM_ * WN_ * 64), 0, s, A, \
+                       lda, M, K_, tiles_m, tiles_n, GM, NB_, VB0_, bsrc, EPI_V)
+#define CC_LAUNCH_NT(BM_, BN_, WM_, WN_)                                                                    \
+    hipLaunchKernelGGL((gemm_nt_kernel<BM_, BN_, WM_, WN_, BSrc, Epi>), dim3(n_tiles), dim3(WM_ * WN_ * 64), 0, \
+                       s, A, lda, M, K, tiles_m, tiles_n, GM, bsrc, epi)
     if (S > 1) {
-        const int64_t ld = (int64_t)tiles_n * 256;
-        EpiPartial pe{ws, ld, (int64_t)M * ld};
-        if (pick == 'b') CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, EpiPartial, pe, K / S);
-        else CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, EpiPartial, pe, K / S);
-        hipLaunchKernelGGL((splitk_finish_kernel<Epi>), dim3(tiles_n, (M + 7) / 8), dim3(256), 0, s, ws, ld,
-                           (int64_t)M * ld, S, M, epi);
+        const int rem = n_tiles % n_cu == 0 ? n_cu : n_tiles % n_cu, full = n_tiles - rem;
+        EpiPartial pe{ws, (int64_t)rem * 65536, 0, 0};
+        if (pick == 'b') {
+            if (full) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K, full, 0, 1);
+            CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, EpiPartial, pe, K / S, rem, full, S);
+        } else {
+            if (full) CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K, full, 0, 1);
+            CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, EpiPartial, pe, K / S, rem, full, S);
+        }
+        hipLaunchKernelGGL((splitk_finish_kernel<Epi>), dim3(rem, (bm + 7) / 8), dim3(256), 0, s, ws,
+                           (int64_t)rem * 65536, S, M, bm, full, tiles_m, tiles_n, GM, epi);
     } else if (pick == 'b') {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K);
-        else CC_LAUNCH(gemm_nt_kernel, 256, 256, 2, 4, Epi, epi, K);
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
+        else CC_LAUNCH_NT(256, 256, 2, 4);
     } else if (pick == 'm') {
-        CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K);
+        CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
     } else if (pick == 'h') {
-        CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2, Epi, epi, K);
+        CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2, Epi, epi, K, n_tiles, 0, 1);
     } else {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 128, 2, 2, Epi, epi, K);
-        else CC_LAUNCH(gemm_nt_kernel, 128, 128, 2, 2, Epi, epi, K);
+        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 128, 2, 2, Epi, epi, K, n_tiles, 0, 1);
+        else CC_LAUNCH_NT(128, 128, 2, 2);
     }
 #undef CC_LAUNCH
+#undef CC_LAUNCH_NT
 }
 
 }  // namespace

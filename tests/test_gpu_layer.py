@@ -358,6 +358,35 @@ def test_stage_projections_against_oracle_pieces(tile, splitk, monkeypatch):
     ctx.close()
 
 
+@pytest.mark.parametrize("splitk,tile", [("2", ""), ("2", "m"), ("3", "")])
+def test_stage_mlp_wide_grid_with_split_last_round(splitk, tile, monkeypatch):
+    """A gate/up grid of 258 tiles (one full round of workgroups and two tiles more): with two K
+    shares forced the full round runs as one launch and the two remaining tiles as split-K with
+    the finishing pass; three shares divide only the down projection's K (2 tiles, split whole)."""
+    monkeypatch.setenv("CC_GEMM_SPLITK", splitk)
+    if tile:
+        monkeypatch.setenv("CC_GEMM_CFG", tile)
+    else:
+        monkeypatch.delenv("CC_GEMM_CFG", raising=False)
+    model = ModelShape(256, 4, 2, 64, 16512, 1e4, 1e-5, False, 1)
+    M = 300
+    rng = np.random.default_rng(11)
+    w = gen.layer_weights(model, 0, seed=33)
+    ctx = _ctx(model, 64, M)
+    dw = dev_weights(w)
+    y = torch.from_numpy(rng.standard_normal((M, model.d)).astype(np.float32)).to(DEV)
+    out = torch.empty((M, model.d), dtype=torch.bfloat16, device=DEV)
+    ctx.step_mlp(y, M, dw.w_post_norm, dw.w_gate, dw.w_up, dw.w_down, out)
+    torch.cuda.synchronize()
+    yf = y.cpu().numpy().astype(np.float64)
+    m = layer.rmsnorm(yf, obf.bits_to_f64(w["w_post_norm"]), model.rms_eps)
+    z = yf + (layer.silu(m @ obf.bits_to_f64(w["w_gate"]).T) * (m @ obf.bits_to_f64(w["w_up"]).T)) \
+        @ obf.bits_to_f64(w["w_down"]).T
+    mx, mn = err_stats(bits_f64(host_bits(out)), z)
+    assert mx <= MAX_ABS and mn <= MEAN_ABS, (mx, mn)
+    ctx.close()
+
+
 # ------------------------------------------------------------ stack and full-size shapes
 def test_two_layer_stack_with_real_stale_caches():
     wl = CONFIGS["C1x2"]
