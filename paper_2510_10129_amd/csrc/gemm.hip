@@ -810,7 +810,9 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     // workgroup rows, each over K/S columns, with S x tiles <= CUs, and a finishing pass; the full
     // rounds before them run as a launch of their own.  256-wide tiles only.  Times in
     // microseconds: 0.8 per 32-column slice of a 256x256 tile, 6 per round for the ends of a tile,
-    // the finishing pass at 4 TB/s.
+    // the finishing pass at 4 TB/s plus 10 for the two extra launches (measured: QKV at M = 3928,
+    // 384 tiles, takes 208 split against 199 with the 192-row tile, so the estimate has to be
+    // 10 % below the unsplit one to be taken).
     int S = 1;
     if (ring && ws) {
         const double slice_us = 0.8 * K / BKS / 65536.0;        // per unit of tile area
@@ -838,7 +840,7 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
                 const int rem = rem_of(bm);
                 for (int sp = 2; sp <= 16; ++sp) {
                     if (!split_ok(bm, sp, 512)) continue;
-                    const double t = full_rounds * (tile_us + 6.0) + tile_us / sp + 6.0 + 4.0 +
+                    const double t = full_rounds * (tile_us + 6.0) + tile_us / sp + 6.0 + 10.0 +
                                      (double)sp * rem * 65536.0 * 4 / 4.0e6;
                     if (t < t_best && t < 0.9 * t_unsplit) t_best = t, S = sp, pick = bm == 256 ? 'b' : 'm';
                 }
