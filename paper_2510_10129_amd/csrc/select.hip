@@ -148,8 +148,8 @@ void cc_launch_block_scores(const cc_blk_args& a, int H, int Q_a, float* score, 
 // Top-k + grouping + compaction in one workgroup of 16 waves.
 //
 // Scores become order-preserving 32-bit keys; the k-th largest key is found by
-// a most-significant-digit-first radix search (4 passes of 8 bits, wave-level
-// aggregated histogram updates); ties at the threshold are ranked by index
+// a most-significant-digit-first radix search (4 passes of 8 bits: LDS histogram,
+// the bin of the k-th key by a suffix sum over the 256 bins); ties at the threshold are ranked by index
 // with wave ballots so that the lowest indices win.  Candidates, passing
 // window starts and chosen tokens are bitmaps in LDS: a window test is a
 // popcount over the words the window spans, and the final compaction is one
@@ -223,27 +223,29 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
                     live = (key & mask) == prefix;
                     digit = (key >> shift) & 255u;
                 }
-                // one LDS atomic per distinct digit in the wave
-                uint64_t todo = __ballot(live);
-                while (todo) {
-                    int leader = __ffsll((long long)todo) - 1;
-                    uint32_t dl = __shfl(digit, leader);
-                    uint64_t same = __ballot(live && digit == dl) & todo;
-                    if (lane == leader) atomicAdd(&hist[dl], (uint32_t)__popcll(same));
-                    todo &= ~same;
-                }
+                if (live) atomicAdd(&hist[digit], 1u);
             }
             __syncthreads();
-            if (tid == 0) {
-                uint32_t cum = 0;
-                int b = 255;
-                for (; b > 0; --b) {
-                    uint32_t h = hist[b];
-                    if (cum + h >= krem) break;
-                    cum += h;
+            // the digit b of the k-th largest key: the largest b with (keys of larger digit) < krem
+            // <= (those + keys of digit b); thread b holds bin b, suffix sums by wave shuffles
+            uint32_t h = 0, inc = 0;                    // bin tid; sum of bins tid .. end of this wave
+            if (tid < 256) {
+                h = inc = hist[tid];
+                for (int off = 1; off < 64; off <<= 1) {
+                    uint32_t o = __shfl_down(inc, off);
+                    if (lane + off < 64) inc += o;
                 }
-                sh_prefix = prefix | ((uint32_t)b << shift);
-                sh_krem = krem - cum;
+                if (lane == 0) wave_tot[wave] = inc;
+            }
+            __syncthreads();
+            if (tid < 256) {
+                uint32_t above = inc - h;               // keys in bins above tid
+                for (int w = wave + 1; w < 4; ++w) above += wave_tot[w];
+                const bool here = tid == 0 ? above < krem : (above < krem && krem <= above + h);
+                if (here) {
+                    sh_prefix = prefix | ((uint32_t)tid << shift);
+                    sh_krem = krem - above;
+                }
             }
             __syncthreads();
             prefix = sh_prefix;
