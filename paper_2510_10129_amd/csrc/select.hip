@@ -215,15 +215,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
             if (tid < 256) hist[tid] = 0;
             __syncthreads();
             for (int base = 0; base < T; base += SEL_THREADS) {
-                int t = base + tid;
-                bool live = false;
-                uint32_t digit = 0;
+                const int t = base + tid;
                 if (t < T) {
-                    uint32_t key = score_key(score[t]);
-                    live = (key & mask) == prefix;
-                    digit = (key >> shift) & 255u;
+                    const uint32_t key = score_key(score[t]);
+                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
                 }
-                if (live) atomicAdd(&hist[digit], 1u);
             }
             __syncthreads();
             // the digit b of the k-th largest key: the largest b with (keys of larger digit) < krem
@@ -256,33 +252,42 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     }
 
     // ---- candidate bitmap; equal keys are taken in index order ----
-    uint32_t carry = 0;
-    for (int base = 0; base < T; base += SEL_THREADS) {
-        int t = base + tid;
-        bool gt = false, eq = false;
-        if (t < T) {
-            if (all) {
-                gt = true;
-            } else if (!none) {
-                uint32_t key = score_key(score[t]);
-                gt = key > kth;
-                eq = key == kth;
+    // Wave w owns the contiguous tokens [w * seg, (w + 1) * seg): it counts its keys equal to the
+    // threshold, the sixteen counts give every wave the rank of its first such key, and a second
+    // walk ranks them 64 at a time by ballot.  One barrier in all.
+    {
+        const int seg = ((T + SEL_WAVES * 64 - 1) / (SEL_WAVES * 64)) * 64;   // tokens per wave, whole words
+        const int t0 = wave * seg, t1 = min(T, t0 + seg);
+        uint32_t n_eq = 0;
+        if (!all && !none) {
+            for (int base = t0; base < t1; base += 64) {
+                const int t = base + lane;
+                const bool eq = t < t1 && score_key(score[t]) == kth;
+                n_eq += (uint32_t)__popcll(__ballot(eq));
             }
         }
-        uint64_t be = __ballot(eq);
-        if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(be);
+        if (lane == 0) wave_tot[wave] = n_eq;
         __syncthreads();
-        uint32_t before = carry, total = 0;
-        for (int w = 0; w < SEL_WAVES; ++w) {
-            uint32_t c = wave_tot[w];
-            if (w < wave) before += c;
-            total += c;
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        for (int base = t0; base < t1; base += 64) {
+            const int t = base + lane;
+            bool gt = false, eq = false;
+            if (t < t1) {
+                if (all) {
+                    gt = true;
+                } else if (!none) {
+                    const uint32_t key = score_key(score[t]);
+                    gt = key > kth;
+                    eq = key == kth;
+                }
+            }
+            const uint64_t be = __ballot(eq);
+            const uint32_t rank = before + (uint32_t)__popcll(be & lane_lt);
+            const uint64_t bc = __ballot(gt || (eq && rank < krem));
+            if (lane == 0) cand[base >> 6] = bc;
+            before += (uint32_t)__popcll(be);
         }
-        uint32_t rank = before + (uint32_t)__popcll(be & lane_lt);
-        bool is_c = gt || (eq && rank < krem);
-        uint64_t bc = __ballot(is_c);
-        if (lane == 0) cand[(base >> 6) + wave] = bc;
-        carry += total;
         __syncthreads();
     }
 
