@@ -89,6 +89,26 @@ def traffic(fetch_csv: str, write_csv: str, calib_bytes: int, cmd: str) -> str:
     return "\n".join(out) + "\n"
 
 
+def mfma(path: str, cmd: str) -> str:
+    """Matrix-pipe utilisation per kernel from SQ counters: SQ_VALU_MFMA_BUSY_CYCLES counts busy
+    cycles per SIMD, SQ_BUSY_CU_CYCLES busy cycles per CU (4 SIMDs each)."""
+    names = ("SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES", "SQ_INSTS_MFMA", "SQ_ACTIVE_INST_VALU",
+             "SQ_ACTIVE_INST_LDS", "SQ_WAVE_CYCLES")
+    per = {n: _per_kernel(path, n) for n in names}
+    out = [f"command: {cmd}",
+           "source: rocprofv3 --pmc (SQ counters, summed over the chip per dispatch), averaged per kernel;",
+           "mfma_util = SQ_VALU_MFMA_BUSY_CYCLES / (4 * SQ_BUSY_CU_CYCLES): share of the cycles in which a CU",
+           "runs a wave during which a SIMD's matrix pipe is busy (in clocks, at whatever clock the card ran)", "",
+           f"{'kind':12s} {'launches':>8} {'mfma_busy_Mcyc':>15} {'cu_busy_Mcyc':>13} {'mfma_insts_M':>13} {'mfma_util':>10}"]
+    for kind in sorted(per["SQ_BUSY_CU_CYCLES"]):
+        busy, n = per["SQ_VALU_MFMA_BUSY_CYCLES"].get(kind, (0.0, 0))
+        cu, _ = per["SQ_BUSY_CU_CYCLES"][kind]
+        insts, _ = per["SQ_INSTS_MFMA"].get(kind, (0.0, 0))
+        util = busy / (4.0 * cu) if cu else 0.0
+        out.append(f"{kind:12s} {n:8d} {busy / 1e6:15.1f} {cu / 1e6:13.1f} {insts / 1e6:13.2f} {util:10.3f}")
+    return "\n".join(out) + "\n"
+
+
 def read_traffic(path: str):
     """Parses the `traffic_bytes_per_launch[kind]: N` lines of a summary written by `traffic`."""
     res = {}
@@ -113,9 +133,14 @@ def main():
     b.add_argument("write_csv")
     b.add_argument("--calib-bytes", type=int, required=True)
     b.add_argument("--cmd", required=True)
+    m = sub.add_parser("mfma")
+    m.add_argument("csv")
+    m.add_argument("--cmd", required=True)
     args = ap.parse_args()
     if args.what == "stats":
         sys.stdout.write(stats(args.csv, args.cmd))
+    elif args.what == "mfma":
+        sys.stdout.write(mfma(args.csv, args.cmd))
     else:
         sys.stdout.write(traffic(args.fetch_csv, args.write_csv, args.calib_bytes, args.cmd))
 
