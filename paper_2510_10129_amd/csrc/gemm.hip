@@ -761,6 +761,271 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
                                               m0, bn, M, epi_for_tile(epi, vb - vb0, m0));
 }
 
+// The same ring with 16x16x32 MFMAs and hand-written fragment reads (256x256 tile only).
+template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
+    const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int GM, int nb, int vb0,
+    BSrc bsrc, Epi epi) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32;
+    constexpr int UM = WM / 16, UN = WN / 16;       // 16x16 accumulator tiles per wave
+    // DMA instructions per wave and slice.  Where the A_P 16-row pieces of A do not divide among
+    // the waves, the first A_FULL waves own A_I pieces and the others A_I - 1; those repeat
+    // their last piece so that every wave issues the same number of loads.
+    constexpr int A_P = BM / 16;
+    constexpr int A_I = (A_P + NW - 1) / NW, B_I = BN / 16 / NW;
+    constexpr int A_FULL = A_P - NW * (A_I - 1);
+    constexpr int DPS = A_I + B_I;
+    constexpr int SL = NW * DPS * 16 * BKS;
+    // rows of a staged fp32 group: 32 if that fits in one slot and a wave's row blocks pair up, else 16
+    constexpr int RG = (32 * BN * 4 <= SL * 2 && TM % (4 / WAVES_M) == 0) ? 32 : 16;
+    static_assert(BM % 16 == 0 && BN % (16 * NW) == 0 && BN % 32 == 0, "tile/waves");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+    static_assert(RG * BN * 4 <= SL * 2, "an fp32 row group fits in one slot");
+    static_assert(DPS * (NS - 1) < 64, "vmcnt range");
+
+    // One array: the fragment reads of this loop are written by hand, so the compiler has no
+    // LDS reads to order against the global -> LDS loads.
+    __shared__ __align__(16) bf16_t ring[NS * SL];
+    auto slot = [&](int i) -> bf16_t* { return ring + i * SL; };
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+    int bm, bn;
+    const int vb = tile_of_block(blockIdx.x, nb, vb0, tiles_m, tiles_n, GM, &bm, &bn);   // this launch covers tiles vb0 .. vb0 + nb - 1
+    const int m0 = bm * BM;
+
+    // One DMA instruction moves 16 slice rows (16 x 64 B).  Lane L fills physical
+    // chunk slot L%4 of row L/4 and fetches the logical chunk slot ^ ((row>>2)&3):
+    // a 16-byte fragment read of 16 consecutive rows then touches every bank once.
+    // Wave w loads its A pieces (16 rows each) and B rows w*16*B_I .. of the tile, and a slot
+    // holds them wave by wave ([wave][A rows | B rows], DPS KB each): the DPS loads of a wave
+    // and slice share one LDS base and differ in their immediate offset only.
+    // Global addresses are a wave-uniform base (advanced along K in scalar
+    // registers) plus a loop-invariant 32-bit lane offset.
+    uint32_t ao[A_I], bo[B_I];
+    const int a_rows = M - m0;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+    for (int i = 0; i < A_I; ++i) {
+        const int piece = wave_u < A_FULL ? wave_u * A_I + i
+                                          : A_FULL * A_I + (wave_u - A_FULL) * (A_I - 1) + (i < A_I - 1 ? i : A_I - 2);
+        int r = piece * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        r = r < a_rows ? r : a_rows - 1;
+        ao[i] = (uint32_t)((r * lda + c * 8) * 2);
+    }
+    // B rows: the rows of one wave lie in one half of the tile (BN/2 is a multiple of
+    // 16*B_I); each half has its own base (the gate and the up matrix of a fused gate/up tile,
+    // or simply row BN/2 of the same matrix).
+    static_assert((BN / 2) % (16 * B_I) == 0, "a wave's B rows stay in one half");
+    const bool hi_half = wave_u * B_I * 16 >= BN / 2;          // wave-uniform
+#pragma unroll
+    for (int i = 0; i < B_I; ++i) {
+        int r = (wave_u * B_I + i) * 16 - (hi_half ? BN / 2 : 0) + (lane >> 2);   // row within the half
+        const int c = (lane & 3) ^ ((r >> 2) & 3);             // same swizzle as for the tile row
+        const int left = bsrc.template rows_left<BN>(bn, hi_half ? 1 : 0);
+        r = r < left ? r : left - 1;
+        bo[i] = (uint32_t)((r * bsrc.ldb + c * 8) * 2);
+    }
+    // K is this launch's share per workgroup row: row blockIdx.y starts blockIdx.y * K columns in
+    const int64_t kz = (int64_t)blockIdx.y * K * 2;
+    const char* abase = reinterpret_cast<const char*>(A + (int64_t)m0 * lda) + kz;
+    const char* bbase = reinterpret_cast<const char*>(bsrc.template base<BN>(bn, hi_half ? 1 : 0)) + kz;
+    const int wbase = wave_u * DPS * 16 * BKS;
+    auto scalar_ptr = [](const char* p) -> const char* {   // keeps the base in scalar registers
+        const uint64_t u = reinterpret_cast<uint64_t>(p);
+        const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
+        const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(u >> 32));
+        return reinterpret_cast<const char*>((hi << 32) | lo);
+    };
+    auto dma_one = [&](bf16_t* s, int sidx, auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        const int64_t kb = (int64_t)sidx * (BKS * 2);
+        if constexpr (i < A_I) {
+            const char* ab = scalar_ptr(abase + kb - i * 1024);   // the immediate adds it back
+            asm volatile("" : "+v"(ao[i]));   // keeps the offset a 32-bit register operand of the load
+            dma16_at<i * 1024>(ab + ao[i], s + wbase);
+        } else {
+            const char* bb = scalar_ptr(bbase + kb - i * 1024);
+            asm volatile("" : "+v"(bo[i - A_I]));
+            dma16_at<i * 1024>(bb + bo[i - A_I], s + wbase);
+        }
+    };
+    auto dma_slice = [&](bf16_t* s, int sidx) __attribute__((always_inline)) {
+        unrolled<DPS>([&](auto i) __attribute__((always_inline)) { dma_one(s, sidx, i); });
+    };
+    // element offset in a slot of tile row r of A (is_b = 0) or B (is_b = 1)
+    auto row_at = [](int r, int is_b) {
+        constexpr int per_b = 16 * B_I;
+        if (is_b) return ((r / per_b) * DPS * 16 + A_I * 16 + r % per_b) * BKS;
+        const int piece = r / 16;
+        int w, i;
+        if (A_FULL == NW || piece < A_FULL * A_I) {
+            w = piece / A_I, i = piece % A_I;
+        } else {
+            const int q = piece - A_FULL * A_I;
+            w = A_FULL + q / (A_I > 1 ? A_I - 1 : 1), i = q % (A_I > 1 ? A_I - 1 : 1);
+        }
+        return (w * DPS * 16 + i * 16 + r % 16) * BKS;
+    };
+
+    // ---- 16x16x32 MFMAs: one k-step per slice.  Lane L holds row (column) L%16 and the eight k
+    //      values of 16-byte chunk L/16 of the slice row; an accumulator tile is f32x4 with
+    //      row 4*(L/16) + v, column L%16 ----
+    static_assert(UM % 4 == 0 && UM >= 4 && UN >= 2 && A_FULL == NW, "fragment ring / piece layout");
+    static_assert(WM % (16 * A_I) == 0 && WN % (16 * B_I) == 0, "fragment offsets are lane-independent");
+    static_assert(DPS <= 2 * UN, "one load per MFMA of a block's first part at most");
+    f32x4 acc[UM][UN];
+#pragma unroll
+    for (int i = 0; i < UM; ++i)
+#pragma unroll
+        for (int j = 0; j < UN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int frow = lane & 15, fk = lane >> 4;
+    const int fsw = (lane >> 2) & 3;
+    const int sl = (fk ^ fsw) << 3;
+    // A fragments cycle through four registers (two rows ahead of the MFMAs), B fragments of a
+    // slice stay for the slice and alternate between two sets from slice to slice
+    bf16x8 ar[4], bq[2][UN];
+    // byte offset of fragment i (16 rows) from the lane's address of fragment 0
+    constexpr auto delta = [](int i, int per, int dps) { return 2 * BKS * (((16 * i) / per) * dps * 16 + (16 * i) % per); };
+    const uint32_t ring_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)ring;
+    const uint32_t a_lane = ring_base + 2 * (row_at(wm0 + frow, 0) + sl), b_lane = ring_base + 2 * (row_at(wn0 + frow, 1) + sl);
+    // slots 0, 1 and 2, 3 share an address register each: the offset field of an LDS read is 16 bits
+    static_assert(NS == 4, "slot pairs");
+    const uint32_t a_addr[2] = {a_lane, a_lane + 2 * 2 * SL}, b_addr[2] = {b_lane, b_lane + 2 * 2 * SL};
+    auto read_a = [&](auto jc, auto ic) __attribute__((always_inline)) -> bf16x8 {
+        constexpr int j = decltype(jc)::value, i = decltype(ic)::value;
+        constexpr int off = (j & 1) * 2 * SL + delta(i, 16 * A_I, DPS);
+        static_assert(off < 65536, "ds offset field");
+        bf16x8 v;
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(a_addr[j >> 1]), "n"(off));
+        return v;
+    };
+    auto read_b = [&](auto jc, auto ic) __attribute__((always_inline)) -> bf16x8 {
+        constexpr int j = decltype(jc)::value, i = decltype(ic)::value;
+        constexpr int off = (j & 1) * 2 * SL + delta(i, 16 * B_I, DPS);
+        static_assert(off < 65536, "ds offset field");
+        bf16x8 v;
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(b_addr[j >> 1]), "n"(off));
+        return v;
+    };
+    // One slice (slot j), straight-line code: [the last two fragment rows of the previous slice,
+    // between their MFMAs the first reads of this slice and the refill of the slot freed at the
+    // previous barrier], rows 0 .. UM-3 (the A fragment two rows ahead is requested before each
+    // row's MFMAs), wait, barrier.  The compiler does not know that a hand-written read fills
+    // its registers later: every read is issued and waited for inside this block, and none is
+    // in flight at its end.  Reads return in issue order (A0 B0 .. B(UN-1) A1 A2 ...): when a
+    // row's MFMAs need their operands, exactly two younger reads may still be out.
+    auto block = [&](auto jc, auto firstc, auto dmac, auto vmc, int sidx) __attribute__((always_inline)) {
+        constexpr int j = decltype(jc)::value, bb = j & 1;
+        constexpr bool first = decltype(firstc)::value, with_dma = decltype(dmac)::value;
+        constexpr int VM = decltype(vmc)::value;
+        unrolled<2 * UN>([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value, i = UM - 2 + m / UN, n = m % UN;
+            if constexpr (!first) acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[i % 4], bq[bb ^ 1][n], acc[i][n], 0, 0, 0);
+            if constexpr (m == 0) ar[0] = read_a(jc, std::integral_constant<int, 0>{});
+            else if constexpr (m <= UN) bq[bb][m - 1] = read_b(jc, std::integral_constant<int, m - 1>{});
+            else if constexpr (m == UN + 1) ar[1] = read_a(jc, std::integral_constant<int, 1>{});
+            if constexpr (with_dma && m < DPS) dma_one(slot((j + NS - 1) % NS), sidx, mc);
+            if constexpr (!first) __builtin_amdgcn_sched_barrier(0);
+        });
+        unrolled<UM - 2>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            ar[(i + 2) % 4] = read_a(jc, std::integral_constant<int, i + 2>{});
+            asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(ar[i % 4]));
+            if constexpr (i == 0) {
+#pragma unroll
+                for (int n = 0; n < UN; ++n) asm volatile("" : "+v"(bq[bb][n]));
+            }
+            unrolled<UN>([&](auto nc) __attribute__((always_inline)) {
+                constexpr int n = decltype(nc)::value;
+                acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[i % 4], bq[bb][n], acc[i][n], 0, 0, 0);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // this wave's loads of the next slice have landed (at most VM younger ones may be out) and
+        // its last two A fragments have arrived; after the barrier slot j is free everywhere
+        asm volatile("s_waitcnt vmcnt(%2) lgkmcnt(0)" : "+v"(ar[2]), "+v"(ar[3]) : "n"(VM));
+        wg_barrier();
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+#define CC_IC(x) std::integral_constant<int, (x)>{}
+    const int KS = K / BKS;            // K % (BKS * NS) == 0, KS >= NS
+#pragma unroll
+    for (int j = 0; j < NS; ++j) dma_slice(slot(j), j);
+    wait_vm_lds0<DPS * (NS - 1)>();
+    wg_barrier();
+    constexpr int VS = DPS * (NS - 2);
+    block(CC_IC(0), T{}, F{}, CC_IC(VS), 0);
+    int t = 1;
+    for (; t + 3 + NS <= KS; t += NS) {      // slices t .. t+3 in slots 1, 2, 3, 0; each refills the slot before its own
+        block(CC_IC(1), F{}, T{}, CC_IC(VS), t - 1 + NS);
+        block(CC_IC(2), F{}, T{}, CC_IC(VS), t + NS);
+        block(CC_IC(3), F{}, T{}, CC_IC(VS), t + 1 + NS);
+        block(CC_IC(0), F{}, T{}, CC_IC(VS), t + 2 + NS);
+    }
+    // t == KS - NS + 1: the last three slices, every load has been issued
+    block(CC_IC(1), F{}, F{}, CC_IC(DPS), 0);
+    block(CC_IC(2), F{}, F{}, CC_IC(0), 0);
+    block(CC_IC(3), F{}, F{}, CC_IC(0), 0);
+#undef CC_IC
+    // rows UM-2, UM-1 of the last slice
+    unrolled<2 * UN>([&](auto mc) __attribute__((always_inline)) {
+        constexpr int m = decltype(mc)::value, i = UM - 2 + m / UN, n = m % UN;
+        acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[i % 4], bq[1][n], acc[i][n], 0, 0, 0);
+    });
+    __syncthreads();   // every wave has finished reading the ring
+
+    // ---- epilogue: the four slots take one 32-row group each as fp32 [32][BN]; a wave's 128 rows
+    //      leave in two phases of two groups.  Column c of staged row r sits at c ^ 16*((r>>2)&3):
+    //      the four 16-lane groups of an accumulator store (rows 4 apart) hit disjoint banks, and
+    //      8-column chunks stay contiguous for the functors ----
+    {
+        constexpr int NT = NW * 64;
+        constexpr int GPW = 4 / WAVES_M;          // staged groups per wave and phase
+        constexpr int PHASES = TM / GPW;
+        constexpr int TPR = BN / 8, RPP = NT / TPR;
+        static_assert(32 * BN * 4 <= SL * 2 && 4 % WAVES_M == 0 && TM % GPW == 0 && 32 % RPP == 0, "epilogue shape");
+        const int wm = wave % WAVES_M;
+        auto stage = [&](int q) -> float* { return reinterpret_cast<float*>(ring + q * SL); };
+        const auto e2 = epi_for_tile(epi, vb - vb0, m0);
+#pragma unroll
+        for (int p = 0; p < PHASES; ++p) {
+            if (p) __syncthreads();
+#pragma unroll
+            for (int g = 0; g < GPW; ++g) {
+                float* st = stage(wm * GPW + g);      // slot q holds wave-row q / GPW, group q % GPW
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {      // the two 16-row accumulator tiles of the group
+                    const int i = (p * GPW + g) * 2 + hh;
+#pragma unroll
+                    for (int jj = 0; jj < UN; ++jj)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int r = 16 * hh + 4 * fk + v;
+                            st[r * BN + ((wn0 + jj * 16 + frow) ^ (fk << 4))] = acc[i][jj][v];
+                        }
+                }
+            }
+            __syncthreads();
+            const int cc = (tid % TPR) * 8;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row0 = (q / GPW) * WM + (p * GPW + q % GPW) * 32;   // tile row of the slot's first row
+#pragma unroll
+                for (int k = 0; k < 32 / RPP; ++k) {
+                    const int r = tid / TPR + k * RPP;
+                    const int m = m0 + row0 + r;
+                    if (m < M) e2.template operator()<BN>(m, bn, cc, stage(q) + r * BN, ((r >> 2) & 3) << 4);
+                }
+            }
+        }
+    }
+}
+
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
 // workgroup per CU), 192x256 (8 waves of 96x64, ring loop only, measured at 0.8 of the
 // large tile's rate: it pays where it saves a half-empty round), 256x128 (8 waves of
@@ -786,6 +1051,8 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     if (force_gm && !*force_gm) force_gm = nullptr;
     const char* force_sk = getenv("CC_GEMM_SPLITK");
     if (force_sk && !*force_sk) force_sk = nullptr;
+    const char* force_mfma = getenv("CC_GEMM_MFMA");          // "32": the 32x32x16 loop for the 256x256 tile too
+    const bool mfma16 = !(force_mfma && force_mfma[0] == '3');
     auto rounds_of = [&](int bm, int bn, int per_cu, int shares) {
         const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn) * shares;
         const long slots = (long)n_cu * per_cu;
@@ -862,7 +1129,10 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     if (S > 1) {
         const int rem = n_tiles % n_cu == 0 ? n_cu : n_tiles % n_cu, full = n_tiles - rem;
         EpiPartial pe{ws, (int64_t)rem * 65536, 0, 0};
-        if (pick == 'b') {
+        if (pick == 'b' && mfma16) {
+            if (full) CC_LAUNCH(gemm_ring16_kernel, 256, 256, 2, 4, Epi, epi, K, full, 0, 1);
+            CC_LAUNCH(gemm_ring16_kernel, 256, 256, 2, 4, EpiPartial, pe, K / S, rem, full, S);
+        } else if (pick == 'b') {
             if (full) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K, full, 0, 1);
             CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, EpiPartial, pe, K / S, rem, full, S);
         } else {
@@ -872,7 +1142,8 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
         hipLaunchKernelGGL((splitk_finish_kernel<Epi>), dim3(rem, (bm + 7) / 8), dim3(256), 0, s, ws,
                            (int64_t)rem * 65536, S, M, bm, full, tiles_m, tiles_n, GM, epi);
     } else if (pick == 'b') {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
+        if (ring && mfma16) CC_LAUNCH(gemm_ring16_kernel, 256, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
+        else if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
         else CC_LAUNCH_NT(256, 256, 2, 4);
     } else if (pick == 'm') {
         CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);

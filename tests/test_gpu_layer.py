@@ -298,13 +298,15 @@ def test_stage_attention_many_column_blocks_long_and_short_rows():
     ctx.close()
 
 
-@pytest.mark.parametrize("tile,splitk", [("", ""), ("b", ""), ("m", ""), ("h", ""), ("s", ""), ("bt", ""), ("st", ""),
-                                         ("", "2"), ("", "3"), ("", "4"), ("m", "2")])
-def test_stage_projections_against_oracle_pieces(tile, splitk, monkeypatch):
+@pytest.mark.parametrize("tile,splitk,mfma", [("", "", ""), ("b", "", ""), ("b", "", "32"), ("m", "", ""), ("h", "", ""),
+                                              ("s", "", ""), ("bt", "", ""), ("st", "", ""), ("", "2", ""), ("", "3", ""),
+                                              ("", "4", ""), ("m", "2", ""), ("b", "2", "32")])
+def test_stage_projections_against_oracle_pieces(tile, splitk, mfma, monkeypatch):
     """Every projection against the oracle's pieces, by default, with each GEMM tile shape and K
-    loop forced, and with 2, 3 and 4 shares of K (3 divides only the down projection's K here, 4
-    leaves a share of exactly one ring of slices); the library reads the switches at every launch."""
-    for name, val in (("CC_GEMM_CFG", tile), ("CC_GEMM_SPLITK", splitk)):
+    loop forced (the 256x256 tile with its 16x16x32 loop and with the 32x32x16 one), and with 2, 3
+    and 4 shares of K (3 divides only the down projection's K here, 4 leaves a share of exactly one
+    ring of slices); the library reads the switches at every launch."""
+    for name, val in (("CC_GEMM_CFG", tile), ("CC_GEMM_SPLITK", splitk), ("CC_GEMM_MFMA", mfma)):
         if val:
             monkeypatch.setenv(name, val)
         else:

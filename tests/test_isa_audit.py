@@ -1,10 +1,11 @@
-"""Static check of the attention kernel's machine code.
+"""Static check of the machine code of the kernels with hand-written LDS reads (attention and
+the 16x16x32 GEMM ring loop).
 
-Its LDS fragment reads are inline assembly with hand-written `s_waitcnt lgkmcnt(n)`: the
+Their LDS fragment reads are inline assembly with hand-written `s_waitcnt lgkmcnt(n)`: the
 compiler does not know that the destination registers of such a read are filled later, so
 nothing may touch them before a wait that covers the read, and no read may be in flight
 across a label, a branch or a barrier (register copies at control-flow joins would move stale
-values).  This test compiles the kernel to assembly and checks exactly that.
+values).  This test compiles the kernels to assembly and checks exactly that.
 """
 import os
 import re
@@ -19,11 +20,12 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
 def _regs(tok):
-    m = re.match(r"[va]\[(\d+):(\d+)\]$", tok)
+    """Vector registers named by an operand: (file, number) pairs, file = 'v' or 'a'."""
+    m = re.match(r"([va])\[(\d+):(\d+)\]$", tok)
     if m:
-        return set(range(int(m.group(1)), int(m.group(2)) + 1))
-    m = re.match(r"[va](\d+)$", tok)
-    return {int(m.group(1))} if m else set()
+        return {(m.group(1), r) for r in range(int(m.group(2)), int(m.group(3)) + 1)}
+    m = re.match(r"([va])(\d+)$", tok)
+    return {(m.group(1), int(m.group(2)))} if m else set()
 
 
 def audit(asm_text):
@@ -100,4 +102,19 @@ def test_attention_kernel_reads_are_waited_for(tmp_path):
     for name, body in kernels:
         seen, bad = audit(body)
         assert seen >= 40, (name, seen)
+        assert not bad, (name, bad[:5])
+
+
+@pytest.mark.skipif(shutil.which(HIPCC) is None, reason="hipcc not found")
+def test_gemm_ring16_kernel_reads_are_waited_for(tmp_path):
+    out = tmp_path / "gemm.s"
+    cmd = [HIPCC, *build.FLAGS, "-S", "--cuda-device-only", "-o", str(out), os.path.join(build.CSRC, "gemm.hip")]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout
+    text = out.read_text()
+    kernels = re.findall(r"^(_ZN\S*gemm_ring16_kernel\S*):[^\n]*\n(.*?)s_endpgm", text, flags=re.S | re.M)
+    assert len(kernels) >= 6, [k[0] for k in kernels]     # four epilogues and two split-K instances
+    for name, body in kernels:
+        seen, bad = audit(body)
+        assert seen >= 12 * 8, (name, seen)               # 12 fragment reads per slice, 8 slice blocks at least
         assert not bad, (name, bad[:5])
