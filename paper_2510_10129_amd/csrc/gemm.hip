@@ -1027,10 +1027,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
 }
 
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
-// workgroup per CU), 192x256 (8 waves of 96x64, ring loop only, measured at 0.8 of the
-// large tile's rate: it pays where it saves a half-empty round), 256x128 (8 waves of
-// 64x64, one per CU, ring loop only) and 128x128 (4 waves of 64x64, two per CU, measured
-// at 0.6 to 0.9 of the large tile's rate depending on K).  A grid runs as a whole number
+// workgroup per CU; its ring loop uses 16x16x32 MFMAs, the other shapes 32x32x16), 192x256
+// (8 waves of 96x64, ring loop only, measured at 0.76 of the large tile's rate: it pays
+// where it saves a half-empty round), 256x128 (8 waves of 64x64, one per CU, ring loop
+// only) and 128x128 (4 waves of 64x64, two per CU, measured at 0.55 to 0.85 of the large
+// tile's rate depending on K).  A grid runs as a whole number
 // of "rounds" of workgroups, so the shape is chosen per launch to minimise rounds x tile
 // cost.
 template <class BSrc, class Epi>
@@ -1065,8 +1066,8 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     bool ring = K % (BKS * NS) == 0 && (int64_t)lda * 256 * 2 < (1ll << 31) &&
                 (int64_t)ldb * 256 * 2 < (1ll << 31);
     if (force && force[0] && force[1] == 't') ring = false;
-    const double cb = cost(256, 256, 1, 1.00), cm = cost(192, 256, 1, 0.80), ch = cost(256, 128, 1, 0.75),
-                 cs = cost(128, 128, 2, 0.72);
+    const double cb = cost(256, 256, 1, 1.00), cm = cost(192, 256, 1, 0.76), ch = cost(256, 128, 1, 0.70),
+                 cs = cost(128, 128, 2, 0.67);
     char pick = cb <= cs ? 'b' : 's';
     double best = cb <= cs ? cb : cs;
     if (ring && ch < best) pick = 'h', best = ch;               // these two have no staged variant
@@ -1076,13 +1077,13 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     // fills at most half the chip (all tiles, if there is no full round) are computed by S
     // workgroup rows, each over K/S columns, with S x tiles <= CUs, and a finishing pass; the full
     // rounds before them run as a launch of their own.  256-wide tiles only.  Times in
-    // microseconds: 0.8 per 32-column slice of a 256x256 tile, 6 per round for the ends of a tile,
+    // microseconds: 0.75 per 32-column slice of a 256x256 tile, 6 per round for the ends of a tile,
     // the finishing pass at 4 TB/s plus 10 for the two extra launches (measured: QKV at M = 3928,
     // 384 tiles, takes 208 split against 199 with the 192-row tile, so the estimate has to be
     // 10 % below the unsplit one to be taken).
     int S = 1;
     if (ring && ws) {
-        const double slice_us = 0.8 * K / BKS / 65536.0;        // per unit of tile area
+        const double slice_us = 0.75 * K / BKS / 65536.0;       // per unit of tile area
         auto rem_of = [&](int bm) {
             const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + 255) / 256);
             return (int)(tiles % n_cu == 0 && tiles > 0 ? n_cu : tiles % n_cu);
@@ -1102,7 +1103,7 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
                                                                pick == 's' ? 2 : 1, 1);
             const double t_unsplit = t_best;
             for (int bm = 256; bm >= 192; bm -= 64) {
-                const double tile_us = bm * 256.0 / (bm == 256 ? 1.0 : 0.8) * slice_us;
+                const double tile_us = bm * 256.0 / (bm == 256 ? 1.0 : 0.76) * slice_us;
                 const long full_rounds = rounds_of(bm, 256, 1, 1) - 1;
                 const int rem = rem_of(bm);
                 for (int sp = 2; sp <= 16; ++sp) {
