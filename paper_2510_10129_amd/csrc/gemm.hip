@@ -761,7 +761,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring_kernel(
                                               m0, bn, M, epi_for_tile(epi, vb - vb0, m0));
 }
 
-// The same ring with 16x16x32 MFMAs and hand-written fragment reads (256x256 tile only).
+// The same ring with 16x16x32 MFMAs and hand-written fragment reads (the 256-wide tiles).
 template <int BM, int BN, int WAVES_M, int WAVES_N, class BSrc, class Epi>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
     const bf16_t* __restrict__ A, int lda, int M, int K, int tiles_m, int tiles_n, int GM, int nb, int vb0,
@@ -874,8 +874,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
     // ---- 16x16x32 MFMAs: one k-step per slice.  Lane L holds row (column) L%16 and the eight k
     //      values of 16-byte chunk L/16 of the slice row; an accumulator tile is f32x4 with
     //      row 4*(L/16) + v, column L%16 ----
-    static_assert(UM % 4 == 0 && UM >= 4 && UN >= 2 && A_FULL == NW, "fragment ring / piece layout");
-    static_assert(WM % (16 * A_I) == 0 && WN % (16 * B_I) == 0, "fragment offsets are lane-independent");
+    static_assert(UM % 2 == 0 && UM >= 4 && UN >= 2, "fragment ring");
+    static_assert((A_FULL != NW || WM % (16 * A_I) == 0) && WN % (16 * B_I) == 0, "fragment offsets are lane-independent");
     static_assert(DPS <= 2 * UN, "one load per MFMA of a block's first part at most");
     f32x4 acc[UM][UN];
 #pragma unroll
@@ -895,12 +895,28 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
     // slots 0, 1 and 2, 3 share an address register each: the offset field of an LDS read is 16 bits
     static_assert(NS == 4, "slot pairs");
     const uint32_t a_addr[2] = {a_lane, a_lane + 2 * 2 * SL}, b_addr[2] = {b_lane, b_lane + 2 * 2 * SL};
+    // Where the pieces of A are not spread evenly (192-row tile) the fragments of a wave are not
+    // at the same distances for both wave rows: one address register per fragment and slot pair.
+    constexpr bool A_EVEN = A_FULL == NW;
+    uint32_t a_fr[A_EVEN ? 1 : UM][2];
+    if constexpr (!A_EVEN) {
+#pragma unroll
+        for (int i = 0; i < UM; ++i) {
+            a_fr[i][0] = ring_base + 2 * (row_at(wm0 + i * 16 + frow, 0) + sl);
+            a_fr[i][1] = a_fr[i][0] + 2 * 2 * SL;
+        }
+    }
     auto read_a = [&](auto jc, auto ic) __attribute__((always_inline)) -> bf16x8 {
         constexpr int j = decltype(jc)::value, i = decltype(ic)::value;
-        constexpr int off = (j & 1) * 2 * SL + delta(i, 16 * A_I, DPS);
-        static_assert(off < 65536, "ds offset field");
         bf16x8 v;
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(a_addr[j >> 1]), "n"(off));
+        if constexpr (A_EVEN) {
+            constexpr int off = (j & 1) * 2 * SL + delta(i, 16 * A_I, DPS);
+            static_assert(off < 65536, "ds offset field");
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(a_addr[j >> 1]), "n"(off));
+        } else {
+            constexpr int off = (j & 1) * 2 * SL;
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(a_fr[i][j >> 1]), "n"(off));
+        }
         return v;
     };
     auto read_b = [&](auto jc, auto ic) __attribute__((always_inline)) -> bf16x8 {
@@ -922,32 +938,36 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
         constexpr int j = decltype(jc)::value, bb = j & 1;
         constexpr bool first = decltype(firstc)::value, with_dma = decltype(dmac)::value;
         constexpr int VM = decltype(vmc)::value;
+        // A fragment i of this slice lives in ar[(i + RO) % 4]; with UM % 4 == 2 the slices of odd
+        // slots start two registers on, so that the previous slice's last two stay clear of the
+        // first two of this one
+        constexpr int RO = (UM % 4) * (j & 1) % 4, RP = (UM % 4) * ((j + NS - 1) & 1) % 4;
         unrolled<2 * UN>([&](auto mc) __attribute__((always_inline)) {
             constexpr int m = decltype(mc)::value, i = UM - 2 + m / UN, n = m % UN;
-            if constexpr (!first) acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[i % 4], bq[bb ^ 1][n], acc[i][n], 0, 0, 0);
-            if constexpr (m == 0) ar[0] = read_a(jc, std::integral_constant<int, 0>{});
+            if constexpr (!first) acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[(i + RP) % 4], bq[bb ^ 1][n], acc[i][n], 0, 0, 0);
+            if constexpr (m == 0) ar[RO % 4] = read_a(jc, std::integral_constant<int, 0>{});
             else if constexpr (m <= UN) bq[bb][m - 1] = read_b(jc, std::integral_constant<int, m - 1>{});
-            else if constexpr (m == UN + 1) ar[1] = read_a(jc, std::integral_constant<int, 1>{});
+            else if constexpr (m == UN + 1) ar[(1 + RO) % 4] = read_a(jc, std::integral_constant<int, 1>{});
             if constexpr (with_dma && m < DPS) dma_one(slot((j + NS - 1) % NS), sidx, mc);
             if constexpr (!first) __builtin_amdgcn_sched_barrier(0);
         });
         unrolled<UM - 2>([&](auto ic) __attribute__((always_inline)) {
             constexpr int i = decltype(ic)::value;
-            ar[(i + 2) % 4] = read_a(jc, std::integral_constant<int, i + 2>{});
-            asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(ar[i % 4]));
+            ar[(i + 2 + RO) % 4] = read_a(jc, std::integral_constant<int, i + 2>{});
+            asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(ar[(i + RO) % 4]));
             if constexpr (i == 0) {
 #pragma unroll
                 for (int n = 0; n < UN; ++n) asm volatile("" : "+v"(bq[bb][n]));
             }
             unrolled<UN>([&](auto nc) __attribute__((always_inline)) {
                 constexpr int n = decltype(nc)::value;
-                acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[i % 4], bq[bb][n], acc[i][n], 0, 0, 0);
+                acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[(i + RO) % 4], bq[bb][n], acc[i][n], 0, 0, 0);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
         // this wave's loads of the next slice have landed (at most VM younger ones may be out) and
         // its last two A fragments have arrived; after the barrier slot j is free everywhere
-        asm volatile("s_waitcnt vmcnt(%2) lgkmcnt(0)" : "+v"(ar[2]), "+v"(ar[3]) : "n"(VM));
+        asm volatile("s_waitcnt vmcnt(%2) lgkmcnt(0)" : "+v"(ar[(UM - 2 + RO) % 4]), "+v"(ar[(UM - 1 + RO) % 4]) : "n"(VM));
         wg_barrier();
     };
     using T = std::true_type;
@@ -972,23 +992,27 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
     block(CC_IC(2), F{}, F{}, CC_IC(0), 0);
     block(CC_IC(3), F{}, F{}, CC_IC(0), 0);
 #undef CC_IC
-    // rows UM-2, UM-1 of the last slice
+    // rows UM-2, UM-1 of the last slice (slot NS-1)
     unrolled<2 * UN>([&](auto mc) __attribute__((always_inline)) {
         constexpr int m = decltype(mc)::value, i = UM - 2 + m / UN, n = m % UN;
-        acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[i % 4], bq[1][n], acc[i][n], 0, 0, 0);
+        constexpr int RL = (UM % 4) * ((NS - 1) & 1) % 4;
+        acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ar[(i + RL) % 4], bq[1][n], acc[i][n], 0, 0, 0);
     });
     __syncthreads();   // every wave has finished reading the ring
 
-    // ---- epilogue: the four slots take one 32-row group each as fp32 [32][BN]; a wave's 128 rows
-    //      leave in two phases of two groups.  Column c of staged row r sits at c ^ 16*((r>>2)&3):
-    //      the four 16-lane groups of an accumulator store (rows 4 apart) hit disjoint banks, and
-    //      8-column chunks stay contiguous for the functors ----
+    // ---- epilogue: the four slots take one RG-row group each as fp32 [RG][BN] (RG = 32: two
+    //      accumulator tiles, where a slot is large enough and a wave's 32-row blocks pair up; else
+    //      16: one), a wave's rows leave in phases of 4 / WAVES_M groups.  Column c of staged row r
+    //      sits at c ^ 16*((r>>2)&3): the four 16-lane groups of an accumulator store (rows 4 apart)
+    //      hit disjoint banks, and 8-column chunks stay contiguous for the functors ----
     {
         constexpr int NT = NW * 64;
         constexpr int GPW = 4 / WAVES_M;          // staged groups per wave and phase
-        constexpr int PHASES = TM / GPW;
+        constexpr int RGS = (32 * BN * 4 <= SL * 2 && TM % GPW == 0) ? 32 : 16;
+        constexpr int TPG = RGS / 16;             // accumulator tiles per group
+        constexpr int PHASES = UM / (GPW * TPG);
         constexpr int TPR = BN / 8, RPP = NT / TPR;
-        static_assert(32 * BN * 4 <= SL * 2 && 4 % WAVES_M == 0 && TM % GPW == 0 && 32 % RPP == 0, "epilogue shape");
+        static_assert(RGS * BN * 4 <= SL * 2 && 4 % WAVES_M == 0 && UM % (GPW * TPG) == 0 && RGS % RPP == 0, "epilogue shape");
         const int wm = wave % WAVES_M;
         auto stage = [&](int q) -> float* { return reinterpret_cast<float*>(ring + q * SL); };
         const auto e2 = epi_for_tile(epi, vb - vb0, m0);
@@ -999,8 +1023,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
             for (int g = 0; g < GPW; ++g) {
                 float* st = stage(wm * GPW + g);      // slot q holds wave-row q / GPW, group q % GPW
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {      // the two 16-row accumulator tiles of the group
-                    const int i = (p * GPW + g) * 2 + hh;
+                for (int hh = 0; hh < TPG; ++hh) {    // the 16-row accumulator tiles of the group
+                    const int i = (p * GPW + g) * TPG + hh;
 #pragma unroll
                     for (int jj = 0; jj < UN; ++jj)
 #pragma unroll
@@ -1014,9 +1038,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
             const int cc = (tid % TPR) * 8;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int row0 = (q / GPW) * WM + (p * GPW + q % GPW) * 32;   // tile row of the slot's first row
+                const int row0 = (q / GPW) * WM + (p * GPW + q % GPW) * RGS;   // tile row of the slot's first row
 #pragma unroll
-                for (int k = 0; k < 32 / RPP; ++k) {
+                for (int k = 0; k < RGS / RPP; ++k) {
                     const int r = tid / TPR + k * RPP;
                     const int m = m0 + row0 + r;
                     if (m < M) e2.template operator()<BN>(m, bn, cc, stage(q) + r * BN, ((r >> 2) & 3) << 4);
@@ -1027,9 +1051,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
 }
 
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
-// workgroup per CU; its ring loop uses 16x16x32 MFMAs, the other shapes 32x32x16), 192x256
-// (8 waves of 96x64, ring loop only, measured at 0.76 of the large tile's rate: it pays
-// where it saves a half-empty round), 256x128 (8 waves of 64x64, one per CU, ring loop
+// workgroup per CU), 192x256 (8 waves of 96x64, ring loop only, measured at 0.8 of the
+// large tile's rate: it pays where it saves a half-empty round; the ring loops of these two
+// use 16x16x32 MFMAs, the other shapes 32x32x16), 256x128 (8 waves of 64x64, one per CU, ring loop
 // only) and 128x128 (4 waves of 64x64, two per CU, measured at 0.55 to 0.85 of the large
 // tile's rate depending on K).  A grid runs as a whole number
 // of "rounds" of workgroups, so the shape is chosen per launch to minimise rounds x tile
@@ -1052,7 +1076,7 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     if (force_gm && !*force_gm) force_gm = nullptr;
     const char* force_sk = getenv("CC_GEMM_SPLITK");
     if (force_sk && !*force_sk) force_sk = nullptr;
-    const char* force_mfma = getenv("CC_GEMM_MFMA");          // "32": the 32x32x16 loop for the 256x256 tile too
+    const char* force_mfma = getenv("CC_GEMM_MFMA");          // "32": the 32x32x16 loop for the 256-wide tiles too
     const bool mfma16 = !(force_mfma && force_mfma[0] == '3');
     auto rounds_of = [&](int bm, int bn, int per_cu, int shares) {
         const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn) * shares;
@@ -1066,7 +1090,7 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     bool ring = K % (BKS * NS) == 0 && (int64_t)lda * 256 * 2 < (1ll << 31) &&
                 (int64_t)ldb * 256 * 2 < (1ll << 31);
     if (force && force[0] && force[1] == 't') ring = false;
-    const double cb = cost(256, 256, 1, 1.00), cm = cost(192, 256, 1, 0.76), ch = cost(256, 128, 1, 0.70),
+    const double cb = cost(256, 256, 1, 1.00), cm = cost(192, 256, 1, 0.80), ch = cost(256, 128, 1, 0.70),
                  cs = cost(128, 128, 2, 0.67);
     char pick = cb <= cs ? 'b' : 's';
     double best = cb <= cs ? cb : cs;
@@ -1103,7 +1127,7 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
                                                                pick == 's' ? 2 : 1, 1);
             const double t_unsplit = t_best;
             for (int bm = 256; bm >= 192; bm -= 64) {
-                const double tile_us = bm * 256.0 / (bm == 256 ? 1.0 : 0.76) * slice_us;
+                const double tile_us = bm * 256.0 / (bm == 256 ? 1.0 : 0.80) * slice_us;
                 const long full_rounds = rounds_of(bm, 256, 1, 1) - 1;
                 const int rem = rem_of(bm);
                 for (int sp = 2; sp <= 16; ++sp) {
@@ -1136,6 +1160,9 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
         } else if (pick == 'b') {
             if (full) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K, full, 0, 1);
             CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, EpiPartial, pe, K / S, rem, full, S);
+        } else if (mfma16) {
+            if (full) CC_LAUNCH(gemm_ring16_kernel, 192, 256, 2, 4, Epi, epi, K, full, 0, 1);
+            CC_LAUNCH(gemm_ring16_kernel, 192, 256, 2, 4, EpiPartial, pe, K / S, rem, full, S);
         } else {
             if (full) CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K, full, 0, 1);
             CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, EpiPartial, pe, K / S, rem, full, S);
@@ -1147,7 +1174,8 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
         else if (ring) CC_LAUNCH(gemm_ring_kernel, 256, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
         else CC_LAUNCH_NT(256, 256, 2, 4);
     } else if (pick == 'm') {
-        CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
+        if (mfma16) CC_LAUNCH(gemm_ring16_kernel, 192, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
+        else CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
     } else if (pick == 'h') {
         CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2, Epi, epi, K, n_tiles, 0, 1);
     } else {
