@@ -1076,7 +1076,7 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     if (force_gm && !*force_gm) force_gm = nullptr;
     const char* force_sk = getenv("CC_GEMM_SPLITK");
     if (force_sk && !*force_sk) force_sk = nullptr;
-    const char* force_mfma = getenv("CC_GEMM_MFMA");          // "32": the 32x32x16 loop for the 256-wide tiles too
+    const char* force_mfma = getenv("CC_GEMM_MFMA");          // "32": the ring loop with 32x32x16 MFMAs
     const bool mfma16 = !(force_mfma && force_mfma[0] == '3');
     auto rounds_of = [&](int bm, int bn, int per_cu, int shares) {
         const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn) * shares;
@@ -1177,9 +1177,11 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
         if (mfma16) CC_LAUNCH(gemm_ring16_kernel, 192, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
         else CC_LAUNCH(gemm_ring_kernel, 192, 256, 2, 4, Epi, epi, K, n_tiles, 0, 1);
     } else if (pick == 'h') {
-        CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2, Epi, epi, K, n_tiles, 0, 1);
+        if (mfma16) CC_LAUNCH(gemm_ring16_kernel, 256, 128, 4, 2, Epi, epi, K, n_tiles, 0, 1);
+        else CC_LAUNCH(gemm_ring_kernel, 256, 128, 4, 2, Epi, epi, K, n_tiles, 0, 1);
     } else {
-        if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 128, 2, 2, Epi, epi, K, n_tiles, 0, 1);
+        if (ring && mfma16) CC_LAUNCH(gemm_ring16_kernel, 128, 128, 2, 2, Epi, epi, K, n_tiles, 0, 1);
+        else if (ring) CC_LAUNCH(gemm_ring_kernel, 128, 128, 2, 2, Epi, epi, K, n_tiles, 0, 1);
         else CC_LAUNCH_NT(128, 128, 2, 2);
     }
 #undef CC_LAUNCH

@@ -328,7 +328,7 @@ def test_stage_attention_many_column_blocks_long_and_short_rows():
 
 @pytest.mark.parametrize("tile,splitk,mfma", [("", "", ""), ("b", "", ""), ("b", "", "32"), ("m", "", ""), ("h", "", ""),
                                               ("s", "", ""), ("bt", "", ""), ("st", "", ""), ("", "2", ""), ("", "3", ""),
-                                              ("", "4", ""), ("m", "2", ""), ("b", "2", "32"), ("m", "", "32"), ("m", "2", "32")])
+                                              ("", "4", ""), ("m", "2", ""), ("b", "2", "32"), ("m", "", "32"), ("m", "2", "32"), ("h", "", "32"), ("s", "", "32")])
 def test_stage_projections_against_oracle_pieces(tile, splitk, mfma, monkeypatch):
     """Every projection against the oracle's pieces, by default, with each GEMM tile shape and K
     loop forced (the 256x256 tile with its 16x16x32 loop and with the 32x32x16 one), and with 2, 3

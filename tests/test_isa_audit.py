@@ -113,8 +113,8 @@ def test_gemm_ring16_kernel_reads_are_waited_for(tmp_path):
     assert r.returncode == 0, r.stdout
     text = out.read_text()
     kernels = re.findall(r"^(_ZN\S*gemm_ring16_kernel\S*):[^\n]*\n(.*?)s_endpgm", text, flags=re.S | re.M)
-    assert len(kernels) >= 12, [k[0] for k in kernels]    # two tile shapes x (four epilogues + two split-K instances)
+    assert len(kernels) >= 20, [k[0] for k in kernels]    # four tile shapes x four epilogues + 2 x two split-K instances
     for name, body in kernels:
         seen, bad = audit(body)
-        assert seen >= 10 * 8, (name, seen)               # 10 or 12 fragment reads per slice, 8 slice blocks
+        assert seen >= 8 * 8, (name, seen)                # 8, 10 or 12 fragment reads per slice, 8 slice blocks
         assert not bad, (name, bad[:5])
