@@ -531,7 +531,13 @@ void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_mo
     // work is taken as half of blocks x t_max (spans grow with the position of the block's last
     // token) with 30 % on top for the uneven end, as measured; plus the merge's traffic.
     const int64_t rows = (int64_t)M * m.H_q;
-    const int n_wg = n_row_tiles * m.H_kv, n_cu = 256;
+    static const int n_cu = [] {
+        int dev = 0, n = 256;
+        if (hipGetDevice(&dev) == hipSuccess)
+            (void)hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        return n > 0 ? n : 256;
+    }();
+    const int n_wg = n_row_tiles * m.H_kv;
     const int t_max = (kv.N + BN_KEYS - 1) / BN_KEYS;
     int S = 1;
     const char* force = getenv("CC_ATTN_SPLITS");     // test switch, read at every launch
