@@ -22,6 +22,14 @@
  *     overlap on different host threads.
  *   - Return value: CC_OK (0) or a negative cc_status.  On error nothing has
  *     been enqueued and no output was written; cc_last_error() gives the text.
+ *   - Launch shapes (GEMM tile, K loop, split-K shares, key splits of the
+ *     attention) are chosen per call from the sizes.  Four environment
+ *     variables, read at every launch, override the choice for tests:
+ *     CC_GEMM_CFG (b, m, h, s = 256x256, 192x256, 256x128, 128x128 tile; a
+ *     second character t = the two-stage K loop), CC_GEMM_MFMA (32 = the ring
+ *     loop with 32x32x16 MFMAs), CC_GEMM_SPLITK (shares of K), CC_ATTN_SPLITS
+ *     (key splits).  Every choice computes the same result up to fp32
+ *     summation order; a value that does not fit the call is ignored.
  */
 #ifndef CACHECLIP_H
 #define CACHECLIP_H
