@@ -107,11 +107,13 @@ def attend_row(q_row: np.ndarray, K: np.ndarray, V: np.ndarray, p: int, g: int):
     H_q, d_h = q_row.shape
     H_kv = H_q // g
     qg = q_row.reshape(H_kv, g, d_h)
-    logits = np.einsum("kgd,jkd->kgj", qg, K[:p + 1]) / np.sqrt(float(d_h))
+    # per kv head k: logits[k] = qg[k] K[:p+1, k, :]^T and o[k] = probs[k] V[:p+1, k, :], as
+    # two batched library matrix products (batch index = kv head)
+    logits = np.matmul(qg, K[:p + 1].transpose(1, 2, 0)) / np.sqrt(float(d_h))      # [H_kv, g, p+1]
     logits = logits - logits.max(axis=-1, keepdims=True)
     e = np.exp(logits)
     probs = e / e.sum(axis=-1, keepdims=True)
-    o = np.einsum("kgj,jkd->kgd", probs, V[:p + 1])
+    o = np.matmul(probs, V[:p + 1].transpose(1, 0, 2))                               # [H_kv, g, d_h]
     return o.reshape(H_q, d_h), probs.reshape(H_q, p + 1)
 
 
