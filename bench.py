@@ -26,8 +26,22 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 CALIB_COPY_BYTES = 1 << 30
 # HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by the calibration copy); written by paper_2510_10129_amd.rocprof_summary from a profiled run
-TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "c3_stack_hbm_traffic_pmc.txt")
+# by the calibration copy): the tracked summary of a profiled run of this program
+TRAFFIC_SUMMARY = os.path.join("profiles", "c3_stack_hbm_traffic_pmc.txt")
+
+
+def read_traffic(path):
+    """The `traffic_bytes_per_launch[kind]: N` lines of the counter summary."""
+    import re
+    res = {}
+    try:
+        for line in open(os.path.join(ROOT, path)):
+            m = re.match(r"traffic_bytes_per_launch\[(\w+)\]: (\d+)", line)
+            if m:
+                res[m.group(1)] = int(m.group(2))
+    except OSError:
+        pass
+    return res
 
 
 def parse():
@@ -175,7 +189,8 @@ def cpu_baseline(wl, model, recomp_bp, n_rows=32):
     rows, t_rows = rows2, t2
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {
-        "value": M / layer_s, "unit": "recomputed tok/s", "cores": threads, "kind": "oracle",
+        "value": M / layer_s, "unit": "recomputed tok/s", "cores": threads, "nproc": os.cpu_count(),
+        "kind": "oracle",
         "ms_per_layer": layer_s * 1e3, "select_ms": t_sel * 1e3, "extrapolated": True,
         "sample": (f"numpy fp64 oracle, one layer of {wl.name}: QKV+RoPE+scatter for all {M} rows "
                    f"({t_kv:.1f} s) + attention/O/MLP for {len(rows)} sampled rows ({t_rows:.1f} s) "
@@ -272,7 +287,6 @@ def main():
             ach = amount / (avg_ms * 1e-3) / 1e9
             kernels[name] = {"avg_ms": round(avg_ms, 5), "launches_per_step": cnt // a.steps, "bound": bound,
                              "achieved_GBs": round(ach, 1), "frac": round(ach / PEAK_HBM_GBS, 4)}
-    from paper_2510_10129_amd.rocprof_summary import read_traffic
     measured = read_traffic(TRAFFIC_SUMMARY) if a.workload == "C3" and not a.exact_idx else {}
     for name in kernels:
         kernels[name]["traffic_bytes"] = measured.get(name)
@@ -284,6 +298,8 @@ def main():
         "peak": PEAK_BF16_TFLOPS if kd["bound"] == "mfma" else PEAK_HBM_GBS,
         "unit": "TFLOP/s" if kd["bound"] == "mfma" else "GB/s",
         "frac": kd["frac"], "traffic": kd["traffic_bytes"], "avg_ms": kd["avg_ms"],
+        # not measured by this run: counters need rocprofv3, the figure is the tracked summary's
+        "traffic_source": TRAFFIC_SUMMARY if kd["traffic_bytes"] is not None else None,
     }
     layer_flops = sum(v for k, (b, v) in work.items() if b == "mfma")
     ms_per_layer = dt * 1e3 / L

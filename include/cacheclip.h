@@ -23,13 +23,12 @@
  *   - Return value: CC_OK (0) or a negative cc_status.  On error nothing has
  *     been enqueued and no output was written; cc_last_error() gives the text.
  *   - Launch shapes (GEMM tile, K loop, split-K shares, key splits of the
- *     attention) are chosen per call from the sizes.  Four environment
- *     variables, read at every launch, override the choice for tests:
- *     CC_GEMM_CFG (b, m, h, s = 256x256, 192x256, 256x128, 128x128 tile; a
- *     second character t = the two-stage K loop), CC_GEMM_MFMA (32 = the ring
- *     loop with 32x32x16 MFMAs), CC_GEMM_SPLITK (shares of K), CC_ATTN_SPLITS
- *     (key splits).  Every choice computes the same result up to fp32
- *     summation order; a value that does not fit the call is ignored.
+ *     attention) are chosen per call from the sizes; cc_debug_set_launch (at
+ *     the end of this file) overrides the choice for tests.
+ *   - Every cache slot below kv->N must hold finite values, also the slots no
+ *     row attends to: a masked key enters the value contraction as probability
+ *     zero times its V row, and zero times NaN or infinity is NaN.
+ *     cc_assemble_cache writes zeros to the slots it does not fill.
  */
 #ifndef CACHECLIP_H
 #define CACHECLIP_H
@@ -260,6 +259,25 @@ cc_status cc_profile_read(cc_ctx* ctx, float* ms, int32_t* count);
  * per dispatch) are calibrated against this kernel, whose traffic is known: `bytes`
  * read and `bytes` written. */
 cc_status cc_calib_copy(cc_ctx* ctx, void* dst, const void* src, int64_t bytes);
+
+/*
+ * Test support: overrides the launch shapes that the library otherwise picks from
+ * the sizes of a call, so that a test can send the same inputs through every tile
+ * shape and loop.  Every choice computes the same result up to the fp32 summation
+ * order; a value that does not fit a call (a tile shape without a variant for the
+ * call's K, more shares than K allows or the workspace holds) is ignored for that
+ * call.  The override stays until the next cc_debug_set_launch on this context;
+ * o == NULL restores the library's own choices.  All-zero fields mean "no override".
+ */
+typedef struct cc_launch_override {
+    int32_t gemm_tile;    /* 0, or 'b' 256x256, 'm' 192x256, 'h' 256x128, 's' 128x128 */
+    int32_t gemm_staged;  /* 1: the two-stage K loop (64 columns per stage) instead of the ring */
+    int32_t gemm_mfma32;  /* 1: the ring loop with 32x32x16 MFMAs instead of 16x16x32 */
+    int32_t gemm_gm;      /* > 0: row tiles per band of the XCD-aware tile order */
+    int32_t gemm_splitk;  /* > 0: shares of K (1 = never split) */
+    int32_t attn_splits;  /* > 0: key splits of the attention launch (1 = never split) */
+} cc_launch_override;
+cc_status cc_debug_set_launch(cc_ctx* ctx, const cc_launch_override* o);
 
 #ifdef __cplusplus
 }

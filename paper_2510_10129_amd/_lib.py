@@ -23,7 +23,7 @@ EXPORTS = (
     "cc_step_column_scores", "cc_recompute_layer", "cc_step_gather_rmsnorm",
     "cc_step_qkv_rope_scatter", "cc_step_sparse_attention", "cc_step_oproj_residual",
     "cc_step_mlp", "cc_profile_enable", "cc_profile_read", "cc_calib_copy", "cc_assemble_cache",
-    "cc_step_block_scores", "cc_select_blocks",
+    "cc_step_block_scores", "cc_select_blocks", "cc_debug_set_launch",
 )
 
 
@@ -56,6 +56,11 @@ class _AuxBlock(C.Structure):
 class _Weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("w_in_norm", "w_qkv", "b_qkv", "w_o", "w_post_norm",
                                           "w_gate", "w_up", "w_down")]
+
+
+class LaunchOverride(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("gemm_tile", "gemm_staged", "gemm_mfma32", "gemm_gm",
+                                         "gemm_splitk", "attn_splits")]
 
 
 def lib_path() -> str:
@@ -101,6 +106,7 @@ def load_library() -> C.CDLL:
     lib.cc_step_block_scores.argtypes = [vp, C.POINTER(_AuxBlock), i32, i32, i32, vp]
     lib.cc_select_blocks.argtypes = [vp, C.POINTER(_AuxBlock), i32, i32, i32, u32, i32, i32, i32, i32, i32,
                                      vp, vp, C.POINTER(i32)]
+    lib.cc_debug_set_launch.argtypes = [vp, C.POINTER(LaunchOverride)]
     lib.cc_profile_enable.argtypes = [vp, i32]
     lib.cc_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     for name in EXPORTS:
@@ -289,6 +295,14 @@ class Context:
     def calib_copy(self, dst, src):
         self._check(self._lib.cc_calib_copy(self._h, dst.data_ptr(), src.data_ptr(),
                                             src.numel() * src.element_size()))
+
+    # ---- test support ----
+    def debug_set_launch(self, gemm_tile: str = "", gemm_staged: bool = False, gemm_mfma32: bool = False,
+                         gemm_gm: int = 0, gemm_splitk: int = 0, attn_splits: int = 0):
+        """Overrides the launch shapes until the next call; no arguments = the library's own choices."""
+        o = LaunchOverride(ord(gemm_tile) if gemm_tile else 0, int(gemm_staged), int(gemm_mfma32), gemm_gm,
+                           gemm_splitk, attn_splits)
+        self._check(self._lib.cc_debug_set_launch(self._h, C.byref(o)))
 
     # ---- timing ----
     def profile_enable(self, on: bool):

@@ -107,6 +107,7 @@ cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream) {
     c->m = *desc;
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->prof = false;
+    memset(&c->ovr, 0, sizeof(c->ovr));
     memset(c->prof_ms, 0, sizeof(c->prof_ms));
     memset(c->prof_n, 0, sizeof(c->prof_n));
     c->rope = nullptr; c->xn = nullptr; c->q = nullptr; c->o = nullptr; c->y = nullptr;
@@ -323,7 +324,7 @@ cc_status cc_step_qkv_rope_scatter(cc_ctx* c, const void* xn, int32_t M, const i
     {
         cc_prof_scope ps(c, CC_K_QKV);
         cc_launch_qkv((const bf16_t*)xn, M, idx, (const bf16_t*)w_qkv, (const bf16_t*)b_qkv, c->m,
-                      c->rope, *kv, (bf16_t*)q_out, c->gemm_part, c->gemm_part_floats, c->stream);
+                      c->rope, *kv, (bf16_t*)q_out, c->gemm_part, c->gemm_part_floats, c->ovr, c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;
@@ -343,7 +344,7 @@ cc_status cc_step_sparse_attention(cc_ctx* c, const void* q, int32_t M, const in
     }
     {
         cc_prof_scope ps(c, CC_K_ATTN);
-        cc_launch_attention((const bf16_t*)q, M, idx, c->m, *kv, (bf16_t*)o, c->attn_part, c->attn_part_rows, c->stream);
+        cc_launch_attention((const bf16_t*)q, M, idx, c->m, *kv, (bf16_t*)o, c->attn_part, c->attn_part_rows, c->ovr, c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;
@@ -359,7 +360,7 @@ cc_status cc_step_oproj_residual(cc_ctx* c, const void* o, int32_t M, const void
     {
         cc_prof_scope ps(c, CC_K_OPROJ);
         cc_launch_oproj((const bf16_t*)o, M, (const bf16_t*)w_o, (const bf16_t*)hidden, gather_idx,
-                        c->m, y, c->gemm_part, c->gemm_part_floats, c->stream);
+                        c->m, y, c->gemm_part, c->gemm_part_floats, c->ovr, c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;
@@ -382,12 +383,12 @@ cc_status cc_step_mlp(cc_ctx* c, const float* y, int32_t M, const void* w_post_n
     {
         cc_prof_scope ps(c, CC_K_GATE_UP);
         cc_launch_gate_up(c->mn, M, (const bf16_t*)w_gate, (const bf16_t*)w_up, c->m, c->act, c->gemm_part,
-                          c->gemm_part_floats, c->stream);
+                          c->gemm_part_floats, c->ovr, c->stream);
     }
     {
         cc_prof_scope ps(c, CC_K_DOWN);
         cc_launch_down(c->act, M, (const bf16_t*)w_down, y, c->m, (bf16_t*)out, c->gemm_part, c->gemm_part_floats,
-                       c->stream);
+                       c->ovr, c->stream);
     }
     CC_HIP(c, hipGetLastError());
     return CC_OK;
@@ -489,6 +490,21 @@ cc_status cc_calib_copy(cc_ctx* c, void* dst, const void* src, int64_t bytes) {
         cc_launch_copy(dst, src, bytes, c->stream);
     }
     CC_HIP(c, hipGetLastError());
+    return CC_OK;
+}
+
+cc_status cc_debug_set_launch(cc_ctx* c, const cc_launch_override* o) {
+    if (!c) return fail(nullptr, CC_ERR_NULL, "ctx must not be NULL");
+    if (!o) {
+        memset(&c->ovr, 0, sizeof(c->ovr));
+        return CC_OK;
+    }
+    const int t = o->gemm_tile;
+    if (t != 0 && t != 'b' && t != 'm' && t != 'h' && t != 's')
+        return fail(c, CC_ERR_SHAPE, "gemm_tile must be 0, 'b', 'm', 'h' or 's'");
+    if (o->gemm_gm < 0 || o->gemm_splitk < 0 || o->gemm_splitk > 16 || o->attn_splits < 0 || o->attn_splits > 64)
+        return fail(c, CC_ERR_SHAPE, "override values must be >= 0, gemm_splitk <= 16, attn_splits <= 64");
+    c->ovr = *o;
     return CC_OK;
 }
 

@@ -40,8 +40,6 @@
 // first and last row of the tile.  Workgroups are issued longest-first and
 // workgroup id modulo H_kv picks the kv head, so the workgroups resident on
 // one XCD walk the same K/V stream through that XCD's L2.
-#include <stdlib.h>
-
 #include "cc_internal.h"
 #include <type_traits>
 
@@ -520,7 +518,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 }  // namespace
 
 void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_model_desc& m,
-                         const cc_kv_layer& kv, bf16_t* o, float* part, int64_t part_rows, hipStream_t s) {
+                         const cc_kv_layer& kv, bf16_t* o, float* part, int64_t part_rows,
+                         const cc_launch_override& ovr, hipStream_t s) {
     if (M <= 0) return;
     const int g = m.H_q / m.H_kv;
     const int n_row_tiles = (int)(((int64_t)M * g + 255) / 256);   // 256 (token, head) columns each
@@ -540,9 +539,8 @@ void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_mo
     const int n_wg = n_row_tiles * m.H_kv;
     const int t_max = (kv.N + BN_KEYS - 1) / BN_KEYS;
     int S = 1;
-    const char* force = getenv("CC_ATTN_SPLITS");     // test switch, read at every launch
-    if (force && *force) {
-        S = atoi(force);
+    if (ovr.attn_splits > 0) {                        // test override (cc_debug_set_launch)
+        S = ovr.attn_splits;
     } else if (part && n_wg < 2 * n_cu) {
         const double tile_us = m.d_h == 128 ? 1.9 : 1.0;
         const double spread = 1.3 * 0.5 * (double)n_wg * t_max / n_cu;

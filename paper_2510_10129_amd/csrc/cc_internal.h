@@ -43,6 +43,7 @@ struct cc_ctx {
     int32_t* n_sel;    // [1]
     int32_t* flag;     // [1] idx check result
     int32_t* pinned;   // host pinned [2]
+    cc_launch_override ovr;   // test overrides of the launch shapes (all zero: none)
 
     // profiling
     bool prof;
@@ -107,14 +108,18 @@ void cc_launch_rmsnorm_f32(const float* y, int M, int d, const bf16_t* w, float 
                            hipStream_t s);
 void cc_launch_qkv(const bf16_t* xn, int M, const int32_t* idx, const bf16_t* w_qkv,
                    const bf16_t* b_qkv, const cc_model_desc& m, const float2* rope,
-                   const cc_kv_layer& kv, bf16_t* q_out, float* ws, int64_t ws_floats, hipStream_t s);
+                   const cc_kv_layer& kv, bf16_t* q_out, float* ws, int64_t ws_floats,
+                   const cc_launch_override& ovr, hipStream_t s);
 // `part` ([part_rows][d_h + 4] fp32, may be NULL) lets a launch with few workgroups split the keys.
 void cc_launch_attention(const bf16_t* q, int M, const int32_t* idx, const cc_model_desc& m,
-                         const cc_kv_layer& kv, bf16_t* o, float* part, int64_t part_rows, hipStream_t s);
+                         const cc_kv_layer& kv, bf16_t* o, float* part, int64_t part_rows,
+                         const cc_launch_override& ovr, hipStream_t s);
 void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hidden,
                      const int32_t* gather_idx, const cc_model_desc& m, float* y, float* ws,
-                     int64_t ws_floats, hipStream_t s);
+                     int64_t ws_floats, const cc_launch_override& ovr, hipStream_t s);
 void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16_t* w_up,
-                       const cc_model_desc& m, bf16_t* act, float* ws, int64_t ws_floats, hipStream_t s);
+                       const cc_model_desc& m, bf16_t* act, float* ws, int64_t ws_floats,
+                       const cc_launch_override& ovr, hipStream_t s);
 void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float* y,
-                    const cc_model_desc& m, bf16_t* out, float* ws, int64_t ws_floats, hipStream_t s);
+                    const cc_model_desc& m, bf16_t* out, float* ws, int64_t ws_floats,
+                    const cc_launch_override& ovr, hipStream_t s);

@@ -7,19 +7,23 @@
 //   GATE_UP B tile = 64 gate rows + 64 up rows; writes silu(gate)*up
 //   DOWN    + residual stream -> bf16 layer output
 //
-// Tiling: one workgroup of WAVES_M x WAVES_N waves computes a BM x BN tile with
-// v_mfma_f32_32x32x16_bf16.  Operands go from global memory straight into LDS
-// (16-byte global->LDS loads, no register staging), XOR-swizzled so that the
-// 16-byte fragment reads are conflict-free on the 64-bank LDS.  Two K loops:
-//   ring   (K % 128 == 0) slices of 32 columns in a ring of four LDS slots; a
-//          slice is requested three slices (96 columns of MFMA work) before it is
-//          read, which hides the L2/fabric latency that a two-stage pipeline
-//          exposes; one barrier per slice, waits by explicit vmcnt.
-//   staged (any K % 64 == 0) two stages of 64 columns, one barrier per stage.
+// Tiling: one workgroup of WAVES_M x WAVES_N waves computes a BM x BN tile.  Operands
+// go from global memory straight into LDS (16-byte global->LDS loads, no register
+// staging), XOR-swizzled so that the 16-byte fragment reads are conflict-free on the
+// 64-bank LDS.  Three K loops:
+//   ring16 (K % 128 == 0; gemm_ring16_kernel, what every projection of the model
+//          widths runs) slices of 32 columns in a ring of four LDS slots; a slice is
+//          requested three slices (96 columns of MFMA work) before it is read, which
+//          hides the L2/fabric latency that a two-stage pipeline exposes; one barrier
+//          per slice, waits by explicit vmcnt; v_mfma_f32_16x16x32_bf16 (one k-step per
+//          slice) with hand-written fragment reads and hand-counted lgkmcnt waits.
+//   ring   (gemm_ring_kernel) the same ring with v_mfma_f32_32x32x16_bf16 and
+//          compiler-scheduled fragment reads; kept as a cross-check behind
+//          cc_debug_set_launch.
+//   staged (any K % 64 == 0; gemm_nt_kernel) two stages of 64 columns, one barrier
+//          per stage, 32x32x16 MFMAs.
 // The accumulators are written back through LDS so that every global store is
 // 16 or 32 contiguous bytes per lane along the row.
-#include <stdlib.h>
-
 #include "cc_internal.h"
 #include <type_traits>
 
@@ -1060,24 +1064,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
 // cost.
 template <class BSrc, class Epi>
 void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int ldb, int gm_big,
-                 BSrc bsrc, Epi epi, float* ws, int64_t ws_floats, hipStream_t s) {
+                 BSrc bsrc, Epi epi, float* ws, int64_t ws_floats, const cc_launch_override& ovr,
+                 hipStream_t s) {
     static const int n_cu = [] {
         int dev = 0, n = 256;
         if (hipGetDevice(&dev) == hipSuccess)
             (void)hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         return n > 0 ? n : 256;
     }();
-    // Test switches, read at every launch: CC_GEMM_CFG = "b" / "m" / "h" / "s" forces the tile shape
-    // (256x256, 192x256, 256x128, 128x128), a second character "t" the staged loop; CC_GEMM_GM
-    // the band height of the tile order; CC_GEMM_SPLITK the number of K shares (1 = none).
-    const char* force = getenv("CC_GEMM_CFG");
-    if (force && !*force) force = nullptr;
-    const char* force_gm = getenv("CC_GEMM_GM");
-    if (force_gm && !*force_gm) force_gm = nullptr;
-    const char* force_sk = getenv("CC_GEMM_SPLITK");
-    if (force_sk && !*force_sk) force_sk = nullptr;
-    const char* force_mfma = getenv("CC_GEMM_MFMA");          // "32": the ring loop with 32x32x16 MFMAs
-    const bool mfma16 = !(force_mfma && force_mfma[0] == '3');
+    // Test overrides (cc_debug_set_launch): tile shape, staged K loop, the 32x32x16 ring loop,
+    // band height of the tile order, number of K shares (1 = none).
+    const char force = (char)ovr.gemm_tile;                   // 0: the launcher's choice
+    const bool mfma16 = !ovr.gemm_mfma32;
     auto rounds_of = [&](int bm, int bn, int per_cu, int shares) {
         const long tiles = (long)((M + bm - 1) / bm) * ((N_tiles_cols + bn - 1) / bn) * shares;
         const long slots = (long)n_cu * per_cu;
@@ -1089,14 +1087,14 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     // ring loop: whole groups of NS slices, 32-bit lane offsets within a tile's rows
     bool ring = K % (BKS * NS) == 0 && (int64_t)lda * 256 * 2 < (1ll << 31) &&
                 (int64_t)ldb * 256 * 2 < (1ll << 31);
-    if (force && force[0] && force[1] == 't') ring = false;
+    if (ovr.gemm_staged) ring = false;
     const double cb = cost(256, 256, 1, 1.00), cm = cost(192, 256, 1, 0.80), ch = cost(256, 128, 1, 0.70),
                  cs = cost(128, 128, 2, 0.67);
     char pick = cb <= cs ? 'b' : 's';
     double best = cb <= cs ? cb : cs;
     if (ring && ch < best) pick = 'h', best = ch;               // these two have no staged variant
     if (ring && cm < best) pick = 'm', best = cm;
-    if (force && (force[0] == 'b' || force[0] == 's' || ((force[0] == 'h' || force[0] == 'm') && ring))) pick = force[0];
+    if (force == 'b' || force == 's' || ((force == 'h' || force == 'm') && ring)) pick = force;
     // Split-K for the part of a grid that leaves most CUs idle: the tiles of a last round that
     // fills at most half the chip (all tiles, if there is no full round) are computed by S
     // workgroup rows, each over K/S columns, with S x tiles <= CUs, and a finishing pass; the full
@@ -1117,11 +1115,11 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
             return (K / (BKS * NS)) % sp == 0 && K / sp >= k_min && (long)rem * sp <= n_cu &&
                    (double)sp * rem * 65536.0 <= (double)ws_floats;
         };
-        if (force_sk) {
-            const int sp = atoi(force_sk);
+        if (ovr.gemm_splitk > 0) {
+            const int sp = ovr.gemm_splitk;
             const int bm = pick == 'm' ? 192 : 256;
             if (sp > 1 && sp <= 16 && split_ok(bm, sp, BKS * NS)) S = sp, pick = bm == 192 ? 'm' : 'b';
-        } else if (!force) {
+        } else if (!force && !ovr.gemm_staged) {
             double t_best = best * slice_us + 6.0 * rounds_of(pick == 's' ? 128 : pick == 'm' ? 192 : 256,
                                                                (pick == 'b' || pick == 'm') ? 256 : 128,
                                                                pick == 's' ? 2 : 1, 1);
@@ -1142,7 +1140,7 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
     const int bm = pick == 's' ? 128 : pick == 'm' ? 192 : 256, bn = (pick == 'b' || pick == 'm') ? 256 : 128;
     const int tiles_m = (M + bm - 1) / bm, tiles_n = (N_tiles_cols + bn - 1) / bn;
     int GM = pick == 's' ? 2 * gm_big : gm_big;
-    if (force_gm) GM = atoi(force_gm);
+    if (ovr.gemm_gm > 0) GM = ovr.gemm_gm;
     GM = GM < 1 ? 1 : (GM > tiles_m ? tiles_m : GM);
     const int n_tiles = tiles_m * tiles_n;
 #define CC_LAUNCH(KERN, BM_, BN_, WM_, WN_, EPI_T, EPI_V, K_, NB_, VB0_, GY_)                              \
@@ -1192,38 +1190,41 @@ void launch_gemm(const bf16_t* A, int lda, int M, int N_tiles_cols, int K, int l
 
 void cc_launch_qkv(const bf16_t* xn, int M, const int32_t* idx, const bf16_t* w_qkv,
                    const bf16_t* b_qkv, const cc_model_desc& m, const float2* rope,
-                   const cc_kv_layer& kv, bf16_t* q_out, float* ws, int64_t ws_floats, hipStream_t s) {
+                   const cc_kv_layer& kv, bf16_t* q_out, float* ws, int64_t ws_floats,
+                   const cc_launch_override& ovr, hipStream_t s) {
     if (M <= 0) return;
     const int N = (m.H_q + 2 * m.H_kv) * m.d_h;
     BSingle b{w_qkv, m.d, N};
     EpiQKV e{idx, b_qkv, rope, m.H_q, m.H_kv, m.d_h, N, q_out,
              (bf16_t*)kv.K, (bf16_t*)kv.V, kv.stride_token, kv.stride_head};
-    launch_gemm(xn, m.d, M, N, m.d, m.d, 4, b, e, ws, ws_floats, s);
+    launch_gemm(xn, m.d, M, N, m.d, m.d, 4, b, e, ws, ws_floats, ovr, s);
 }
 
 void cc_launch_oproj(const bf16_t* o, int M, const bf16_t* w_o, const bf16_t* hidden,
                      const int32_t* gather_idx, const cc_model_desc& m, float* y, float* ws,
-                     int64_t ws_floats, hipStream_t s) {
+                     int64_t ws_floats, const cc_launch_override& ovr, hipStream_t s) {
     if (M <= 0) return;
     const int K = m.H_q * m.d_h;
     BSingle b{w_o, K, m.d};
     EpiOProj e{hidden, gather_idx, m.d, y};
-    launch_gemm(o, K, M, m.d, K, K, 4, b, e, ws, ws_floats, s);
+    launch_gemm(o, K, M, m.d, K, K, 4, b, e, ws, ws_floats, ovr, s);
 }
 
 void cc_launch_gate_up(const bf16_t* mn, int M, const bf16_t* w_gate, const bf16_t* w_up,
-                       const cc_model_desc& m, bf16_t* act, float* ws, int64_t ws_floats, hipStream_t s) {
+                       const cc_model_desc& m, bf16_t* act, float* ws, int64_t ws_floats,
+                       const cc_launch_override& ovr, hipStream_t s) {
     if (M <= 0) return;
     BDual b{w_gate, w_up, m.d, m.f};
     EpiGateUp e{m.f, act};
     // each 128-column tile holds 64 gate + 64 up columns: 2*f tile columns in total
-    launch_gemm(mn, m.d, M, 2 * m.f, m.d, m.d, 4, b, e, ws, ws_floats, s);
+    launch_gemm(mn, m.d, M, 2 * m.f, m.d, m.d, 4, b, e, ws, ws_floats, ovr, s);
 }
 
 void cc_launch_down(const bf16_t* act, int M, const bf16_t* w_down, const float* y,
-                    const cc_model_desc& m, bf16_t* out, float* ws, int64_t ws_floats, hipStream_t s) {
+                    const cc_model_desc& m, bf16_t* out, float* ws, int64_t ws_floats,
+                    const cc_launch_override& ovr, hipStream_t s) {
     if (M <= 0) return;
     BSingle b{w_down, m.f, m.d};
     EpiDown e{y, m.d, out};
-    launch_gemm(act, m.f, M, m.d, m.f, m.f, 8, b, e, ws, ws_floats, s);
+    launch_gemm(act, m.f, M, m.d, m.f, m.f, 8, b, e, ws, ws_floats, ovr, s);
 }
