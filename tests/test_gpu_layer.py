@@ -92,6 +92,20 @@ SHAPES = [
 ]
 
 
+def _shape_idx(kind, N, rng):
+    if kind == "all":
+        return np.arange(N)
+    if kind == "tail":
+        return np.arange(N - 9, N)
+    if kind == "single":
+        return np.array([77])
+    marks = np.zeros(N, bool)
+    for s in rng.integers(1, N - 10, size=N // 12):
+        marks[s:s + int(rng.integers(1, 9))] = True
+    marks[N - 5:] = True
+    return np.nonzero(marks)[0]
+
+
 @pytest.mark.parametrize("model,N,kind", SHAPES)
 def test_shapes_and_edge_cases(model, N, kind):
     rng = np.random.default_rng(N)
@@ -103,21 +117,23 @@ def test_shapes_and_edge_cases(model, N, kind):
     w["w_qkv"] = gen.f32_to_bf16_bits(wq)
     xl, xg = _x_bits(N, model.d, 1), _x_bits(N, model.d, 2)
     Ks, Vs = fixture.stale_cache_one_layer(xl, w, model)
-    if kind == "all":
-        idx = np.arange(N)
-    elif kind == "tail":
-        idx = np.arange(N - 9, N)
-    elif kind == "single":
-        idx = np.array([77])
-    else:
-        marks = np.zeros(N, bool)
-        for s in rng.integers(1, N - 10, size=N // 12):
-            marks[s:s + int(rng.integers(1, 9))] = True
-        marks[N - 5:] = True
-        idx = np.nonzero(marks)[0]
+    idx = _shape_idx(kind, N, rng)
     got, ref = _run_layer(model, xg, idx, Ks, Vs, idx, w)
     # K/V are three times the recipe's size here and bf16 spacing grows with them
     _assert_layer(got, ref, Ks, Vs, idx, f"{kind} d={model.d} g={model.g} d_h={model.d_h}", kv_scale=3.0)
+
+
+@pytest.mark.parametrize("model,N,kind", SHAPES)
+def test_shapes_and_edge_cases_recipe_weights_strict_bound(model, N, kind):
+    """The same shapes and index sets (a tail, a single row, every row, groups of 7 and of 32
+    query heads, head dims 64 and 128, bias) with the weights of the input recipe as they are:
+    the stated bound, 2e-2 / 2e-3, with no allowance."""
+    rng = np.random.default_rng(N)
+    w = gen.layer_weights(model, 0, seed=N)
+    xl, xg = _x_bits(N, model.d, 1), _x_bits(N, model.d, 2)
+    Ks, Vs = fixture.stale_cache_one_layer(xl, w, model)
+    got, ref = _run_layer(model, xg, (idx := _shape_idx(kind, N, rng)), Ks, Vs, idx, w)
+    _assert_layer(got, ref, Ks, Vs, idx, f"strict {kind} d={model.d} g={model.g} d_h={model.d_h}")
 
 
 @pytest.mark.parametrize("seed", range(10))
@@ -240,15 +256,11 @@ def test_idx_check_and_argument_errors():
 
 # ------------------------------------------------------------ single stages
 @pytest.mark.parametrize("splits", ["", "1", "2", "3", "8"])
-def test_stage_attention_peaked_random(splits, monkeypatch):
+def test_stage_attention_peaked_random(splits):
     """The attention kernel alone, on q/K/V drawn directly so that the softmax is
     sharply peaked and the causal boundary matters; with the launcher's own choice of key
-    splits and with 1, 2, 3 and 8 forced (the library reads CC_ATTN_SPLITS at every launch;
-    more splits than key tiles leave empty parts)."""
-    if splits:
-        monkeypatch.setenv("CC_ATTN_SPLITS", splits)
-    else:
-        monkeypatch.delenv("CC_ATTN_SPLITS", raising=False)
+    splits and with 1, 2, 3 and 8 forced (cc_debug_set_launch; more splits than key tiles
+    leave empty parts)."""
     for (H_q, H_kv, d_h, N, seed) in ((8, 2, 128, 700, 0), (4, 4, 64, 333, 1), (7, 1, 128, 190, 2),
                                       (16, 2, 64, 1000, 3)):
         rng = np.random.default_rng(seed)
@@ -262,6 +274,7 @@ def test_stage_attention_peaked_random(splits, monkeypatch):
         Kb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
         Vb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
         ctx = _ctx(model, N, M)
+        ctx.debug_set_launch(attn_splits=int(splits) if splits else 0)
         o = torch.empty((M, H_q * d_h), dtype=torch.bfloat16, device=DEV)
         ctx.step_sparse_attention(dev_bf16(qb).view(M, -1), M, dev_i32(idx),
                                   cc.KVLayer(dev_bf16(Kb), dev_bf16(Vb)), o, _lib.FLAG_CHECK_IDX)
@@ -326,19 +339,91 @@ def test_stage_attention_many_column_blocks_long_and_short_rows():
     ctx.close()
 
 
+@pytest.mark.parametrize("splits", [1, 2])
+def test_stage_attention_score_jumps_on_both_sides_of_the_rescale_threshold(splits):
+    """The kernel moves the reference point of its base-2 exponent only when a row's maximum
+    grows by more than 8 (a factor 2^8); below that it keeps the old reference and accumulates
+    probabilities up to 256.  Both branches by construction: queries and keys live on one
+    coordinate, q = (a, 0, ..), K[j] = (b_j, 0, ..) with b_j constant over each 64-key tile (0,
+    1, 2.25, 1.5, -3), so the score in base-2 units of every key of tile t is c * b_t with
+    c = a * log2(e) / sqrt(d_h), exactly (one bf16 product per score).  Rows, by their c: a jump
+    of 7.96 over the reference (kept), 8.03 (moved), one move then a keep, two moves, falling
+    scores, and neighbours in one wave that decide differently.  V is random, so an unscaled or
+    doubly scaled accumulator shows in the output."""
+    H_q, H_kv, d_h = 2, 1, 128
+    n_tiles = 5
+    N = 64 * n_tiles + 40
+    b_tile = np.array([0.0, 1.0, 2.25, 1.5, -3.0, 0.5])
+    a_vals = np.array([27.75, 28.0, 58.5, 67.0, -20.0, 3.0, 27.75, 67.0, 28.0, 0.0])    # all exact in bf16
+    k = np.log2(np.e) / np.sqrt(float(d_h))
+    c = a_vals * k
+    assert 7.9 < c[0] * 2.25 < 7.99 and 8.01 < c[1] * 2.25 < 8.1          # just under / just over, tile 2
+    assert 7.3 < c[2] * 1.0 < 7.99 and c[2] * 2.25 - 0.0 > 8.01           # kept at tile 1, moved at tile 2
+    assert c[3] * 1.0 > 8.01 and c[3] * 2.25 - c[3] * 1.0 > 8.01          # moved twice
+    idx = np.arange(N - 20, N)                      # every row sees all five tiles and part of a sixth
+    M = len(idx)
+    rng = np.random.default_rng(42)
+    q = np.zeros((M, H_q, d_h), np.float32)
+    for i in range(M):
+        for h in range(H_q):
+            q[i, h, 0] = a_vals[(2 * i + h) % len(a_vals)]
+    K = np.zeros((N, H_kv, d_h), np.float32)
+    K[:, 0, 0] = b_tile[np.arange(N) // 64]
+    K[:, 0, 1:] = rng.standard_normal((N, d_h - 1))            # q is zero there: no effect on the scores
+    V = rng.standard_normal((N, H_kv, d_h)).astype(np.float32)
+    qb, Kb, Vb = (gen.f32_to_bf16_bits(x) for x in (q, K, V))
+    assert np.array_equal(gen.bf16_to_f32(qb), q) and np.array_equal(gen.bf16_to_f32(Kb)[:, 0, 0], K[:, 0, 0])
+    model = ModelShape(H_q * d_h, H_q, H_kv, d_h, 64, 1e4, 1e-5, False, 1)
+    ctx = _ctx(model, N, M)
+    ctx.debug_set_launch(attn_splits=splits)
+    o = torch.full((M, H_q * d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ctx.step_sparse_attention(dev_bf16(qb).view(M, -1), M, dev_i32(idx),
+                              cc.KVLayer(dev_bf16(Kb), dev_bf16(Vb)), o, _lib.FLAG_CHECK_IDX)
+    torch.cuda.synchronize()
+    qf, Kf, Vf = obf.bits_to_f64(qb), obf.bits_to_f64(Kb), obf.bits_to_f64(Vb)
+    ref = np.stack([layer.attend_row(qf[i], Kf, Vf, int(idx[i]), H_q // H_kv)[0].reshape(-1) for i in range(M)])
+    got = bits_f64(host_bits(o))
+    mx, mn = err_stats(got, ref)
+    print(f"score jumps, {splits} split(s): max {mx:.2e} mean {mn:.2e}")
+    assert mx <= MAX_ABS and mn <= MEAN_ABS, (mx, mn)
+    ctx.close()
+
+
+def test_stage_attention_never_reads_past_the_valid_slots():
+    """The cache allocation is longer than kv->N and holds NaN beyond it: the last key tile is
+    cut at N (loads are clamped to slot N-1), so nothing of it reaches the output."""
+    H_q, H_kv, d_h, N, extra = 4, 2, 128, 150, 64
+    rng = np.random.default_rng(9)
+    model = ModelShape(H_q * d_h, H_q, H_kv, d_h, 64, 1e4, 1e-5, False, 1)
+    idx = np.array([0, 5, 63, 64, 100, 149])
+    M = len(idx)
+    qb = gen.f32_to_bf16_bits(rng.standard_normal((M, H_q, d_h)).astype(np.float32))
+    Kb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+    Vb = gen.f32_to_bf16_bits(rng.standard_normal((N, H_kv, d_h)).astype(np.float32))
+    nan = np.full((extra, H_kv, d_h), 0x7FC0, np.uint16)
+    Kd, Vd = dev_bf16(np.concatenate([Kb, nan])), dev_bf16(np.concatenate([Vb, nan]))
+    ctx = _ctx(model, N, M)
+    o = torch.full((M, H_q * d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ctx.step_sparse_attention(dev_bf16(qb).view(M, -1), M, dev_i32(idx), cc.KVLayer(Kd[:N], Vd[:N]), o,
+                              _lib.FLAG_CHECK_IDX)
+    torch.cuda.synchronize()
+    qf, Kf, Vf = obf.bits_to_f64(qb), obf.bits_to_f64(Kb), obf.bits_to_f64(Vb)
+    ref = np.stack([layer.attend_row(qf[i], Kf, Vf, int(idx[i]), H_q // H_kv)[0].reshape(-1) for i in range(M)])
+    got = bits_f64(host_bits(o))
+    assert np.isfinite(got).all()
+    mx, mn = err_stats(got, ref)
+    assert mx <= MAX_ABS and mn <= MEAN_ABS, (mx, mn)
+    ctx.close()
+
+
 @pytest.mark.parametrize("tile,splitk,mfma", [("", "", ""), ("b", "", ""), ("b", "", "32"), ("m", "", ""), ("h", "", ""),
                                               ("s", "", ""), ("bt", "", ""), ("st", "", ""), ("", "2", ""), ("", "3", ""),
                                               ("", "4", ""), ("m", "2", ""), ("b", "2", "32"), ("m", "", "32"), ("m", "2", "32"), ("h", "", "32"), ("s", "", "32")])
-def test_stage_projections_against_oracle_pieces(tile, splitk, mfma, monkeypatch):
+def test_stage_projections_against_oracle_pieces(tile, splitk, mfma):
     """Every projection against the oracle's pieces, by default, with each GEMM tile shape and K
     loop forced (the 256x256 tile with its 16x16x32 loop and with the 32x32x16 one), and with 2, 3
     and 4 shares of K (3 divides only the down projection's K here, 4 leaves a share of exactly one
-    ring of slices); the library reads the switches at every launch."""
-    for name, val in (("CC_GEMM_CFG", tile), ("CC_GEMM_SPLITK", splitk), ("CC_GEMM_MFMA", mfma)):
-        if val:
-            monkeypatch.setenv(name, val)
-        else:
-            monkeypatch.delenv(name, raising=False)
+    ring of slices); forced through cc_debug_set_launch."""
     model = ModelShape(512, 8, 2, 64, 768, 1e4, 1e-5, True, 1)
     N, M = 500, 203
     rng = np.random.default_rng(5)
@@ -346,6 +431,8 @@ def test_stage_projections_against_oracle_pieces(tile, splitk, mfma, monkeypatch
     xb = _x_bits(N, model.d, 8)
     idx = np.sort(rng.choice(N, size=M, replace=False))
     ctx = _ctx(model, N, M)
+    ctx.debug_set_launch(gemm_tile=tile[:1], gemm_staged=tile.endswith("t"), gemm_mfma32=mfma == "32",
+                         gemm_splitk=int(splitk) if splitk else 0)
     dw = dev_weights(w)
     hid = dev_bf16(xb)
     # R1 gather + RMSNorm
@@ -389,20 +476,16 @@ def test_stage_projections_against_oracle_pieces(tile, splitk, mfma, monkeypatch
 
 
 @pytest.mark.parametrize("splitk,tile", [("2", ""), ("2", "m"), ("3", "")])
-def test_stage_mlp_wide_grid_with_split_last_round(splitk, tile, monkeypatch):
+def test_stage_mlp_wide_grid_with_split_last_round(splitk, tile):
     """A gate/up grid of 258 tiles (one full round of workgroups and two tiles more): with two K
     shares forced the full round runs as one launch and the two remaining tiles as split-K with
     the finishing pass; three shares divide only the down projection's K (2 tiles, split whole)."""
-    monkeypatch.setenv("CC_GEMM_SPLITK", splitk)
-    if tile:
-        monkeypatch.setenv("CC_GEMM_CFG", tile)
-    else:
-        monkeypatch.delenv("CC_GEMM_CFG", raising=False)
     model = ModelShape(256, 4, 2, 64, 16512, 1e4, 1e-5, False, 1)
     M = 300
     rng = np.random.default_rng(11)
     w = gen.layer_weights(model, 0, seed=33)
     ctx = _ctx(model, 64, M)
+    ctx.debug_set_launch(gemm_tile=tile, gemm_splitk=int(splitk))
     dw = dev_weights(w)
     y = torch.from_numpy(rng.standard_normal((M, model.d)).astype(np.float32)).to(DEV)
     out = torch.empty((M, model.d), dtype=torch.bfloat16, device=DEV)
@@ -498,7 +581,24 @@ def test_whole_request_on_the_device(prefix):
     ctx.close()
 
 
-def _sampled_layer_case(name, bp, n_rows, seed):
+def _stratified_rows(M, g, n_extra, seed):
+    """The rows whose layer output is compared in a full-size case: the first and the last, one
+    (drawn at random) in every block of 256 (token, head) columns that an attention workgroup
+    owns, one in every aligned group of 128 rows where those blocks are wider than that (every
+    128-, 192- and 256-row GEMM tile then holds a sampled row), and n_extra more at random."""
+    rng = np.random.default_rng(seed)
+    cols = M * g
+    picks = [0, M - 1]
+    for b in range((cols + 255) // 256):
+        picks.append(int(rng.integers(256 * b, min(cols, 256 * b + 256))) // g)
+    if 256 // g > 64:
+        for r0 in range(0, M, 128):
+            picks.append(int(rng.integers(r0, min(M, r0 + 128))))
+    picks += [int(v) for v in rng.choice(M, size=min(n_extra, M), replace=False)]
+    return np.unique(np.asarray(picks, dtype=np.int64))
+
+
+def _sampled_layer_case(name, bp, n_extra, seed):
     wl = CONFIGS[name]
     model = replace(wl.model, n_layers=1)
     w = gen.layer_weights(model, 0, wl.seed)
@@ -507,15 +607,14 @@ def _sampled_layer_case(name, bp, n_rows, seed):
     Ks[wl.P + wl.T:], Vs[wl.P + wl.T:] = 0, 0
     idx = gen.exact_ratio_idx(wl, bp)
     M = len(idx)
-    rows = np.sort(np.random.default_rng(seed).choice(M, size=n_rows, replace=False))
-    rows[0], rows[-1] = 0, M - 1
+    rows = _stratified_rows(M, model.g, n_extra, seed)
     got, ref = _run_layer(model, xg, idx, Ks, Vs, idx, w, rows=rows)
-    _assert_layer(got, ref, Ks, Vs, idx, f"{name}@{bp // 100}% M={M}")
+    _assert_layer(got, ref, Ks, Vs, idx, f"{name}@{bp // 100}% M={M} ({len(rows)} rows compared)")
 
 
-@pytest.mark.parametrize("bp", [1000, 4000])
+@pytest.mark.parametrize("bp", [1000, 2000, 4000])
 def test_llama8b_layer_4k_sampled_rows(bp):
-    _sampled_layer_case("C2", bp, 24, bp)
+    _sampled_layer_case("C2", bp, 16, bp)
 
 
 def test_llama8b_layer_16k_bench_shape_sampled_rows():
@@ -523,11 +622,12 @@ def test_llama8b_layer_16k_bench_shape_sampled_rows():
     _sampled_layer_case("C3", 2000, 16, 7)
 
 
-def _device_drawn_layer_case(name, bp, n_rows, seed):
+def _device_drawn_layer_case(name, bp, n_extra, seed, dense=False):
     """One layer at a config's full size with inputs drawn on the device (torch's
     generator; the host streams would take minutes at these sizes) and copied to the
     host for the oracle, which projects keys and values for every recomputed row and
-    evaluates attention and the rest of the layer for a sample of rows."""
+    evaluates attention and the rest of the layer for a stratified sample of rows.
+    dense: every cache slot is recomputed (idx = 0..N-1), the full-prefill launch."""
     from workloads import gen_device
     wl = CONFIGS[name]
     model = replace(wl.model, n_layers=1)
@@ -537,10 +637,9 @@ def _device_drawn_layer_case(name, bp, n_rows, seed):
     Kd, Vd = gen_device.cache(wl, 0, dev)
     w = {k: (None if v is None else host_bits(v)) for k, v in wd.items()}
     xg, Ks, Vs = host_bits(hid), host_bits(Kd), host_bits(Vd)
-    idx = gen.exact_ratio_idx(wl, bp)
+    idx = np.arange(wl.N, dtype=np.int32) if dense else gen.exact_ratio_idx(wl, bp)
     M = len(idx)
-    rows = np.sort(np.random.default_rng(seed).choice(M, size=n_rows, replace=False))
-    rows[0], rows[-1] = 0, M - 1
+    rows = _stratified_rows(M, model.g, n_extra, seed)
     ctx = _ctx(model, wl.N, M)
     out = torch.full((M, model.d), float("nan"), dtype=torch.bfloat16, device=dev)
     didx = dev_i32(idx)
@@ -552,14 +651,25 @@ def _device_drawn_layer_case(name, bp, n_rows, seed):
     del wd, hid, Kd, Vd, out
     torch.cuda.empty_cache()
     ref = layer.recompute_layer(xg, idx, Ks, Vs, idx, w, model, rows=rows, q_for_rows_only=True)
-    _assert_layer(got, ref, Ks, Vs, idx, f"{name}@{bp // 100}% M={M}")
+    tag = f"{name} dense" if dense else f"{name}@{bp // 100}%"
+    _assert_layer(got, ref, Ks, Vs, idx, f"{tag} M={M} ({len(rows)} rows compared)")
 
 
-def test_qwen7b_layer_29k_ragged_chunks_sampled_rows():
-    """C4: 28 q / 4 kv heads (groups of 7), QKV bias, chunk lengths U[256,1536]."""
-    _device_drawn_layer_case("C4", 2000, 12, 11)
+@pytest.mark.parametrize("bp", [500, 2000, 5000])
+def test_qwen7b_layer_29k_ragged_chunks_sampled_rows(bp):
+    """C4: 28 q / 4 kv heads (groups of 7), QKV bias, chunk lengths U[256,1536]; 5 % (split
+    attention, split-K projections), 20 % and 50 % (the most rows of any config)."""
+    _device_drawn_layer_case("C4", bp, 16, 11 + bp)
 
 
 def test_llama70b_layer_64k_sampled_rows():
     """C5: d = 8192, 64 q / 8 kv heads, 64k context."""
-    _device_drawn_layer_case("C5", 2000, 8, 12)
+    _device_drawn_layer_case("C5", 2000, 32, 12)
+
+
+def test_llama8b_layer_16k_every_slot_recomputed():
+    """Full prefill on the same kernels, at the size bench.py times it (Section 5.1 "Full
+    Attention", the reference point of the efficiency table of Section 5.6): every one of the
+    16576 cache slots of the 16k workload is recomputed in one call (idx = 0..N-1).  Every K/V row
+    against the oracle, the layer output on the stratified sample."""
+    _device_drawn_layer_case("C3", 0, 16, 13, dense=True)
