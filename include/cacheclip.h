@@ -104,7 +104,8 @@ enum {
 cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream);
 cc_status cc_destroy(cc_ctx* ctx);
 cc_status cc_set_stream(cc_ctx* ctx, void* hip_stream);
-/* Text of the last error on this context (or of the last failed cc_create when ctx is NULL). */
+/* Text of the last error on this context (ctx == NULL: of the last failed cc_create or
+ * context-free call on this thread). */
 const char* cc_last_error(const cc_ctx* ctx);
 
 /*
@@ -131,6 +132,23 @@ cc_status cc_select(cc_ctx* ctx, const float* attn, int32_t Q_a, int32_t T, int6
                     uint32_t recomp_bp, int32_t window, int32_t tau, int32_t flags,
                     int32_t idx_offset, int32_t n_tail,
                     int32_t* idx_out, int32_t* n_out, int32_t* n_out_host);
+
+/*
+ * cc_select for callers that cannot allocate device memory or create a context: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as cc_select, except: no context (the work is enqueued on
+ * `hip_stream`, a hipStream_t or NULL for the default stream, of the current device), no
+ * host copy of the count, and the scores between the two kernels live in a static device
+ * array inside the library (1 MiB per GPU, held until the process ends) instead of a
+ * context's workspace.  T may be at most 131072; a larger T returns CC_ERR_WORKSPACE.
+ * The call allocates and frees nothing and does not synchronise.  Every call on one GPU
+ * uses that GPU's one array: calls that may overlap on a GPU (different streams, different
+ * threads) race on it and must be serialised by the caller; calls on one stream are
+ * ordered.  The error text of a failed call is read with cc_last_error(NULL).
+ */
+cc_status cc_select_noalloc(void* hip_stream, const float* attn, int32_t Q_a, int32_t T, int64_t ld,
+                            uint32_t recomp_bp, int32_t window, int32_t tau, int32_t flags,
+                            int32_t idx_offset, int32_t n_tail, int32_t* idx_out, int32_t* n_out);
 
 /* One batch element of the auxiliary model's last-layer attention (Section 4.2:
  * the chunks are processed as `chunk c + query` in one batch): fp32 attention

@@ -8,5 +8,5 @@ if the library has not been built.
 """
 from ._lib import (  # noqa: F401
     CacheClipError, Context, LayerWeights, KVLayer, ModelDesc, lib_path, load_library,
-    K_NAMES,
+    K_NAMES, select_noalloc,
 )

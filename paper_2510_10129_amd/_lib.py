@@ -23,7 +23,7 @@ EXPORTS = (
     "cc_step_column_scores", "cc_recompute_layer", "cc_step_gather_rmsnorm",
     "cc_step_qkv_rope_scatter", "cc_step_sparse_attention", "cc_step_oproj_residual",
     "cc_step_mlp", "cc_profile_enable", "cc_profile_read", "cc_calib_copy", "cc_assemble_cache",
-    "cc_step_block_scores", "cc_select_blocks", "cc_debug_set_launch",
+    "cc_step_block_scores", "cc_select_blocks", "cc_debug_set_launch", "cc_select_noalloc",
 )
 
 
@@ -93,6 +93,7 @@ def load_library() -> C.CDLL:
     lib.cc_last_error.restype = C.c_char_p
     lib.cc_select.argtypes = [vp, vp, i32, i32, i64, u32, i32, i32, i32, i32, i32, vp, vp,
                               C.POINTER(i32)]
+    lib.cc_select_noalloc.argtypes = [vp, vp, i32, i32, i64, u32, i32, i32, i32, i32, i32, vp, vp]
     lib.cc_step_column_scores.argtypes = [vp, vp, i32, i32, i64, vp]
     lib.cc_recompute_layer.argtypes = [vp, vp, i64, vp, C.POINTER(_KV), vp, i32,
                                        C.POINTER(_Weights), vp, i32]
@@ -114,6 +115,20 @@ def load_library() -> C.CDLL:
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
+
+
+def select_noalloc(attn, recomp_bp: int, window: int, tau: int, flags: int, idx_offset: int, n_tail: int,
+                   idx_out, n_out, stream=None):
+    """cc_select_noalloc: attn cuda fp32 [Q_a, T]; idx_out, n_out preallocated cuda int32.  Enqueues on
+    `stream` (default: torch's current stream); raises CacheClipError on a non-zero status."""
+    import torch
+    lib = load_library()
+    Q_a, T = attn.shape
+    s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    st = lib.cc_select_noalloc(C.c_void_p(s), attn.data_ptr(), Q_a, T, attn.stride(0), recomp_bp, window, tau,
+                               flags, idx_offset, n_tail, idx_out.data_ptr(), n_out.data_ptr())
+    if st != CC_OK:
+        raise CacheClipError(st, (lib.cc_last_error(None) or b"").decode())
 
 
 def _ptr(t) -> Optional[int]:

@@ -2,13 +2,46 @@
 // Every compute step runs in the HIP kernels of this directory.
 #include <math.h>
 #include <algorithm>
+#include <mutex>
 #include <string.h>
 
 #include "cc_internal.h"
 
+// Scratch of cc_select_noalloc: the importance scores between its two kernels live here
+// instead of in a context's workspace.  One copy per GPU, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; the device address it yields (one
+// per device) is what kernels, copies and fills are given.
+#define CC_NOALLOC_T_MAX 131072
+#define CC_NOALLOC_SCRATCH_BYTES (1u << 20)       // scores [T_MAX] fp32 in the first half; the rest is spare
+static __device__ __align__(256) unsigned char scratch[CC_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_create_err;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};            // device address of `scratch` on each device
+
+// Device address of the scratch array on the current device, resolved once per device with
+// that device current.
+hipError_t scratch_on_current_device(void** out, int* dev_out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    if (dev_out) *dev_out = dev;
+    return hipSuccess;
+}
 
 cc_status fail(cc_ctx* c, cc_status code, const std::string& msg) {
     if (c) c->err = msg; else g_create_err = msg;
@@ -116,6 +149,12 @@ cc_status cc_create(cc_ctx** out, const cc_model_desc* desc, void* hip_stream) {
     const cc_model_desc& m = c->m;
     const size_t Mc = (size_t)m.M_cap, nq = (size_t)m.H_q * m.d_h;
     hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) {
+        // resolves the scratch of cc_select_noalloc on this device now, so that a later call
+        // from a region that must not touch the runtime's loader (graph capture) finds it
+        void* sp = nullptr;
+        e = scratch_on_current_device(&sp, nullptr);
+    }
     auto alloc = [&](void** p, size_t bytes) {
         if (e == hipSuccess) e = hipMalloc(p, bytes);
     };
@@ -288,6 +327,33 @@ cc_status cc_select(cc_ctx* c, const float* attn, int32_t Q_a, int32_t T, int64_
         CC_HIP(c, hipStreamSynchronize(c->stream));
         *n_out_host = c->pinned[1];
     }
+    return CC_OK;
+}
+
+cc_status cc_select_noalloc(void* hip_stream, const float* attn, int32_t Q_a, int32_t T, int64_t ld,
+                            uint32_t recomp_bp, int32_t window, int32_t tau, int32_t flags,
+                            int32_t idx_offset, int32_t n_tail, int32_t* idx_out, int32_t* n_out) {
+    if (!attn || !idx_out || !n_out) return fail(nullptr, CC_ERR_NULL, "attn, idx_out and n_out must not be NULL");
+    if (Q_a < 1 || T < 1 || ld < T) return fail(nullptr, CC_ERR_SHAPE, "need Q_a >= 1, T >= 1, ld >= T");
+    if (T > CC_NOALLOC_T_MAX)
+        return fail(nullptr, CC_ERR_WORKSPACE, "T exceeds 131072, the most chunk tokens the static scratch holds scores for");
+    if (recomp_bp > 10000u) return fail(nullptr, CC_ERR_SHAPE, "recomp_bp must be <= 10000");
+    if (window < 1 || window > 1024) return fail(nullptr, CC_ERR_SHAPE, "window must be in [1, 1024]");
+    if (tau < 0 || tau > window) return fail(nullptr, CC_ERR_SHAPE, "tau must be in [0, window]");
+    if (n_tail < 0 || idx_offset < 0) return fail(nullptr, CC_ERR_SHAPE, "idx_offset and n_tail must be >= 0");
+    void* sp = nullptr;
+    hipError_t e = scratch_on_current_device(&sp, nullptr);
+    if (e != hipSuccess)
+        return fail(nullptr, CC_ERR_HIP, std::string("address of the static scratch: ") + hipGetErrorString(e));
+    float* score = static_cast<float*>(sp);           // [T]: every entry below T is written before it is read
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int k = (int)(((int64_t)T * (int64_t)recomp_bp) / 10000);
+    const int tau_eff = tau > 0 ? tau : (5 * window + 7) / 8;
+    cc_launch_colsum(attn, Q_a, T, ld, score, stream);
+    cc_launch_select(score, T, k, window, tau_eff, (flags & CC_FLAG_NO_GROUPING) ? 0 : 1, idx_offset, n_tail,
+                     idx_out, n_out, stream);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(nullptr, CC_ERR_HIP, std::string("launch: ") + hipGetErrorString(e));
     return CC_OK;
 }
 
