@@ -61,6 +61,9 @@ def parse():
                     help="skip timing the HBM-bound kernels at the C5 shape (where they run long enough to measure)")
     ap.add_argument("--hbm-only", action="store_true",
                     help="run only the HBM-bound kernels at the C5 shape and print their figures (for profiling)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="time the vendor BLAS (torch.nn.functional.linear) at the four projection shapes of the "
+                         "workload and print its figures: a reference point for the GEMM kernels, not part of the path")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one copy of 1 GiB through cc_calib_copy (for counter calibration under rocprofv3 --pmc)")
     return ap.parse_args()
@@ -148,6 +151,69 @@ def hbm_kernels_c5(dev, reps=20):
     return out
 
 
+def select_total(dev, names=("C3", "C5"), reps=100):
+    """Token selection as one unit (column sums, top-k, grouping, compaction: two kernels): mean
+    time of a cc_select call when calls follow each other on the stream without a host
+    synchronisation, bracketed by one pair of events on that stream; the bytes are the score
+    block read once plus the index list written."""
+    import torch
+    import paper_2510_10129_amd as cc
+    from workloads import CONFIGS, gen
+    out = {}
+    for name in names:
+        wl = CONFIGS[name]
+        A = torch.from_numpy(gen.aux_attention(wl)).to(dev)
+        ctx = cc.Context.for_model(wl.model, N_cap=64, M_cap=64, T_cap=wl.T)
+        idx = torch.empty(wl.T + wl.Q, dtype=torch.int32, device=dev)
+        n = torch.empty(1, dtype=torch.int32, device=dev)
+        bp = wl.recomp_bp[len(wl.recomp_bp) // 2]
+        call = lambda: ctx.select(A, bp, wl.window, wl.tau, 0, wl.P, wl.Q, idx_out=idx, n_out=n, sync=False)
+        for _ in range(5):
+            call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        M = int(n.item())
+        nbytes = wl.Q_a * wl.T * 4 + M * 4
+        out[name] = {"us_per_call": round(us, 2), "Q_a": wl.Q_a, "T": wl.T, "recomp_bp": bp, "M": M, "bytes": nbytes,
+                     "achieved_GBs": round(nbytes / (us * 1e-6) / 1e9, 1),
+                     "frac": round(nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}
+        ctx.close()
+    return out
+
+
+def vendor_gemm(model, M, dev, reps=20):
+    """The plain products of the four projections through the vendor BLAS (no fused epilogue:
+    no RoPE/scatter, residual, SwiGLU or cast), for scale next to the library's kernels."""
+    import torch
+    F = torch.nn.functional
+    nq = model.H_q * model.d_h
+    shapes = {"qkv": (model.d, model.n_qkv), "oproj": (nq, model.d), "gate_up": (model.d, 2 * model.f),
+              "down": (model.f, model.d)}
+    out = {}
+    for name, (K, N) in shapes.items():
+        x = torch.randn((M, K), dtype=torch.float32, device=dev).to(torch.bfloat16)
+        w = (torch.randn((N, K), dtype=torch.float32, device=dev) * model.sigma_in).to(torch.bfloat16)
+        for _ in range(3):
+            F.linear(x, w)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            F.linear(x, w)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        tf = 2.0 * M * K * N / (ms * 1e-3) / 1e12
+        out[name] = {"M": M, "K": K, "N": N, "avg_ms": round(ms, 5), "achieved_TFLOPs": round(tf, 1),
+                     "frac": round(tf / PEAK_BF16_TFLOPS, 4)}
+        del x, w
+    return out
+
+
 def cpu_baseline(wl, model, recomp_bp, n_rows=32):
     """The oracle as it stands, on the host cores: selection in full; one layer with
     the K/V update (steps 1-4) for all M rows and attention + the rest of the layer
@@ -219,8 +285,15 @@ def main():
         wl = replace(wl, model=model)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
+    if a.vendor_gemm:
+        from workloads import gen as _gen
+        M = len(_gen.exact_ratio_idx(wl, a.recomp_bp)) if a.exact_idx else 3928 if a.workload == "C3" else \
+            len(_gen.exact_ratio_idx(wl, a.recomp_bp))
+        print(json.dumps({"vendor_blas_reference": vendor_gemm(model, M, dev),
+                          "note": "torch.nn.functional.linear, bf16, same box; M = rows the selective step recomputes"}))
+        return
     if a.hbm_only:
-        print(json.dumps({"hbm_kernels_at_C5_shape": hbm_kernels_c5(dev)}))
+        print(json.dumps({"hbm_kernels_at_C5_shape": hbm_kernels_c5(dev), "select_total": select_total(dev)}))
         return
 
     # ---- inputs, resident in HBM ----
@@ -352,6 +425,7 @@ def main():
         del weights, caches, bufs, X
         torch.cuda.empty_cache()
         res["hbm_kernels_at_C5_shape"] = hbm_kernels_c5(dev)
+        res["select_total"] = select_total(dev)
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, model, a.recomp_bp)
     print(json.dumps(res))

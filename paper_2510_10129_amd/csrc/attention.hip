@@ -286,7 +286,11 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kt][v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+        {   // the other half-wave's maximum of the same query row: lanes i and i + 32 exchange by a
+            // register swap (no LDS round trip)
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2;
+        }
         // The reference point m_run of the exponent is only moved when a row's maximum
         // grew by more than 2^8: until then probabilities up to 256 are accumulated
         // (harmless in fp32 / bf16, and the final division by the row sum cancels it),

@@ -522,7 +522,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
         // of the 128 bits (word i, word i + 1), fetched as two 32-bit funnel shifts
         const uint32_t m0 = (uint32_t)wmask, m1 = (uint32_t)(wmask >> 32);
         const uint32_t* c32 = reinterpret_cast<const uint32_t*>(cand);
-#pragma unroll 4
         for (int i = wave; i < n_words; i += SEL_WAVES) {
             const uint32_t* wp = c32 + 2 * i + (lane >> 5);      // word n_words is zero padding
             const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2];

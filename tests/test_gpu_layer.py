@@ -535,6 +535,64 @@ def test_two_layer_stack_with_real_stale_caches():
     ctx.close()
 
 
+def test_eight_layer_stack_drift_at_the_4k_shape(capsys):
+    """How far a stack drifts: eight Llama-3-8B-shaped layers of the 4k workload at 20 %, (a) each
+    layer on the oracle's own input for that layer (teacher-forced: the per-layer bound must hold
+    at every depth) and (b) chained on the device's own outputs against the oracle chained on
+    its own (recorded: rounding differences ride the residual stream, so this error grows with
+    depth; bounded here only against a blow-up).  Weights, hidden rows and stale caches are
+    drawn on the device; every row of every layer is compared."""
+    from workloads import gen_device
+    n_layers = 8
+    wl = CONFIGS["C2"]
+    model = replace(wl.model, n_layers=n_layers)
+    wl = replace(wl, model=model)
+    dev = torch.device(DEV)
+    idx = gen.exact_ratio_idx(wl, 2000)
+    M = len(idx)
+    hid = gen_device.hidden(wl, dev)
+    x_bits = host_bits(hid)
+    ctx = _ctx(model, wl.N, M)
+    didx = dev_i32(idx)
+    h_dev, g_dev = hid, didx                 # the device's own chain
+    h_ref, g_ref = x_bits, idx               # the oracle's own chain
+    lines = []
+    for l in range(n_layers):
+        wd = gen_device.layer_weights(model, l, wl.seed, dev)
+        Kd0, Vd0 = gen_device.cache(wl, l, dev)
+        w = {k: (None if v is None else host_bits(v)) for k, v in wd.items()}
+        Ks, Vs = host_bits(Kd0), host_bits(Vd0)
+        ref = layer.recompute_layer(h_ref, g_ref, Ks, Vs, idx, w, model)           # all M rows: the next layer needs them
+        dw = cc.LayerWeights(**wd)
+        # (a) teacher-forced: the device gets the oracle's input of this layer
+        Kd, Vd = Kd0.clone(), Vd0.clone()
+        out_tf = torch.empty((M, model.d), dtype=torch.bfloat16, device=dev)
+        h_tf = hid if l == 0 else dev_bf16(h_ref)
+        ctx.recompute_layer(h_tf, didx if l == 0 else None, cc.KVLayer(Kd, Vd), didx, M, dw, out_tf,
+                            _lib.FLAG_CHECK_IDX)
+        torch.cuda.synchronize()
+        got = dict(out=host_bits(out_tf), K=host_bits(Kd), V=host_bits(Vd))
+        _assert_layer(got, ref, Ks, Vs, idx, f"stack layer {l} teacher-forced")
+        tf_mx, tf_mn = err_stats(bits_f64(got["out"]), ref.out)
+        # (b) chained: the device continues from its own output
+        Kc, Vc = Kd0, Vd0
+        out_ch = torch.empty((M, model.d), dtype=torch.bfloat16, device=dev)
+        ctx.recompute_layer(h_dev, g_dev, cc.KVLayer(Kc, Vc), didx, M, dw, out_ch, 0)
+        torch.cuda.synchronize()
+        ch_mx, ch_mn = err_stats(bits_f64(host_bits(out_ch)), ref.out)
+        kv_mx, _ = err_stats(bits_f64(host_bits(Kc)[idx]), ref.k_new)
+        lines.append(f"layer {l}: teacher-forced out max {tf_mx:.2e} mean {tf_mn:.2e} | chained out max {ch_mx:.2e} "
+                     f"mean {ch_mn:.2e}, K max {kv_mx:.2e} | rms(out) {np.sqrt(np.mean(ref.out ** 2)):.2f}")
+        assert np.isfinite(bits_f64(host_bits(out_ch))).all()
+        assert ch_mn <= 10 * MEAN_ABS and ch_mx <= 0.5, (l, ch_mx, ch_mn)          # no blow-up with depth
+        h_dev, g_dev = out_ch, None
+        h_ref, g_ref = ref.out_bits, None
+        del wd, dw, Kd, Vd, Kd0, Vd0
+    ctx.close()
+    with capsys.disabled():
+        print(f"\nstack drift, 8 layers of the 4k shape at 20 percent (M = {M}):\n  " + "\n  ".join(lines))
+
+
 @pytest.mark.parametrize("prefix", [16, 0])
 def test_whole_request_on_the_device(prefix):
     """A request from the offline artefacts to the last layer's output, every step on the
