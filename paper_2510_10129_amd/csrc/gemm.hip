@@ -801,8 +801,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
     const int m0 = bm * BM;
 
     // One DMA instruction moves 16 slice rows (16 x 64 B).  Lane L fills physical
-    // chunk slot L%4 of row L/4 and fetches the logical chunk slot ^ ((row>>2)&3):
-    // a 16-byte fragment read of 16 consecutive rows then touches every bank once.
+    // chunk slot L%4 of row L/4 and fetches the logical chunk slot ^ ((row>>1)&3).  The
+    // fragment read of this loop (lane = row L%16, chunk L/16 of 16 consecutive rows) runs at
+    // the full LDS rate with this swizzle and at half of it with slot ^ ((row>>2)&3), with
+    // slot ^ (row&3) or without one (measured with a read-only kernel on this part; the
+    // bank-conflict counter of the loop agrees: half of the active LDS cycles before).
     // Wave w loads its A pieces (16 rows each) and B rows w*16*B_I .. of the tile, and a slot
     // holds them wave by wave ([wave][A rows | B rows], DPS KB each): the DPS loads of a wave
     // and slice share one LDS base and differ in their immediate offset only.
@@ -816,7 +819,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
         const int piece = wave_u < A_FULL ? wave_u * A_I + i
                                           : A_FULL * A_I + (wave_u - A_FULL) * (A_I - 1) + (i < A_I - 1 ? i : A_I - 2);
         int r = piece * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        const int c = (lane & 3) ^ ((r >> 1) & 3);
         r = r < a_rows ? r : a_rows - 1;
         ao[i] = (uint32_t)((r * lda + c * 8) * 2);
     }
@@ -828,7 +831,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
 #pragma unroll
     for (int i = 0; i < B_I; ++i) {
         int r = (wave_u * B_I + i) * 16 - (hi_half ? BN / 2 : 0) + (lane >> 2);   // row within the half
-        const int c = (lane & 3) ^ ((r >> 2) & 3);             // same swizzle as for the tile row
+        const int c = (lane & 3) ^ ((r >> 1) & 3);             // same swizzle as for the tile row
         const int left = bsrc.template rows_left<BN>(bn, hi_half ? 1 : 0);
         r = r < left ? r : left - 1;
         bo[i] = (uint32_t)((r * bsrc.ldb + c * 8) * 2);
@@ -887,7 +890,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
 #pragma unroll
         for (int j = 0; j < UN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int frow = lane & 15, fk = lane >> 4;
-    const int fsw = (lane >> 2) & 3;
+    const int fsw = (lane >> 1) & 3;
     const int sl = (fk ^ fsw) << 3;
     // A fragments cycle through four registers (two rows ahead of the MFMAs), B fragments of a
     // slice stay for the slice and alternate between two sets from slice to slice
