@@ -61,6 +61,8 @@ def parse():
                     help="skip timing the HBM-bound kernels at the C5 shape (where they run long enough to measure)")
     ap.add_argument("--hbm-only", action="store_true",
                     help="run only the HBM-bound kernels at the C5 shape and print their figures (for profiling)")
+    ap.add_argument("--select-only", action="store_true",
+                    help="run only the selection (column sums + top-k/grouping) at the C3 and C5 shapes and print its figures")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="time the vendor BLAS (torch.nn.functional.linear) at the four projection shapes of the "
                          "workload and print its figures: a reference point for the GEMM kernels, not part of the path")
@@ -217,7 +219,8 @@ def vendor_gemm(model, M, dev, reps=20):
 def cpu_baseline(wl, model, recomp_bp, n_rows=32):
     """The oracle as it stands, on the host cores: selection in full; one layer with
     the K/V update (steps 1-4) for all M rows and attention + the rest of the layer
-    (steps 5-7) for a few sampled rows, scaled to M rows."""
+    (steps 5-7) for all M rows if that fits about 20 s of CPU time, else for a sample of
+    rows scaled to M rows (then marked extrapolated)."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import layer as olayer
@@ -234,33 +237,42 @@ def cpu_baseline(wl, model, recomp_bp, n_rows=32):
     w = gen.layer_weights(model, 0, wl.seed)
     _, xg = gen.hidden_pair(wl)
     Kb, Vb = gen.random_cache(wl)
-    # the all-row part (rows=[]) is timed in full; the per-row part is timed at two
-    # sample sizes so that the fixed cost (widening the weights) is not scaled with M
+    # the all-row part (rows=[]) is timed in full; the per-row part in full too when that stays
+    # within the time budget (estimated from a first sample), else at two sample sizes so that
+    # the fixed cost (widening the weights) is not scaled with M
     rng = np.random.default_rng(0)
-    n1, n2 = min(n_rows, M), min(4 * n_rows, M)
+    n1 = min(n_rows, M)
     rows1 = np.sort(rng.choice(M, size=n1, replace=False))
-    rows2 = np.sort(rng.choice(M, size=n2, replace=False))
     t0 = time.perf_counter()
     olayer.recompute_layer(xg, idx, Kb, Vb, idx, w, model, rows=[])
     t_kv = time.perf_counter() - t0
     t0 = time.perf_counter()
     olayer.recompute_layer(xg, idx, Kb, Vb, idx, w, model, rows=rows1)
     t1 = time.perf_counter() - t0 - t_kv
+    budget_s = 20.0
+    n2 = M if t1 * M / max(n1, 1) <= budget_s else min(M, max(4 * n1, int(n1 * budget_s / max(t1, 1e-6))))
+    rows2 = np.arange(M) if n2 == M else np.sort(rng.choice(M, size=n2, replace=False))
     t0 = time.perf_counter()
     olayer.recompute_layer(xg, idx, Kb, Vb, idx, w, model, rows=rows2)
     t2 = time.perf_counter() - t0 - t_kv
-    per_row = max((t2 - t1) / max(n2 - n1, 1), 1e-9)
-    fixed = max(t1 - n1 * per_row, 0.0)
-    layer_s = t_kv + fixed + per_row * M
+    extrapolated = n2 < M
+    if extrapolated:
+        per_row = max((t2 - t1) / max(n2 - n1, 1), 1e-9)
+        fixed = max(t1 - n1 * per_row, 0.0)
+        layer_s = t_kv + fixed + per_row * M
+    else:
+        layer_s = t_kv + t2
     rows, t_rows = rows2, t2
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {
         "value": M / layer_s, "unit": "recomputed tok/s", "cores": threads, "nproc": os.cpu_count(),
         "kind": "oracle",
-        "ms_per_layer": layer_s * 1e3, "select_ms": t_sel * 1e3, "extrapolated": True,
+        "ms_per_layer": layer_s * 1e3, "select_ms": t_sel * 1e3, "extrapolated": extrapolated,
         "sample": (f"numpy fp64 oracle, one layer of {wl.name}: QKV+RoPE+scatter for all {M} rows "
-                   f"({t_kv:.1f} s) + attention/O/MLP for {len(rows)} sampled rows ({t_rows:.1f} s) "
-                   f"and {n1} rows, per-row slope scaled to {M} rows; selection in full ({t_sel * 1e3:.0f} ms)"),
+                   f"({t_kv:.1f} s) + attention/O/MLP for "
+                   + (f"{len(rows)} sampled rows ({t_rows:.1f} s) and {n1} rows, per-row slope scaled to {M} rows"
+                      if extrapolated else f"all {M} rows ({t_rows:.1f} s)")
+                   + f"; selection in full ({t_sel * 1e3:.0f} ms)"),
     }
 
 
@@ -293,7 +305,10 @@ def main():
                           "note": "torch.nn.functional.linear, bf16, same box; M = rows the selective step recomputes"}))
         return
     if a.hbm_only:
-        print(json.dumps({"hbm_kernels_at_C5_shape": hbm_kernels_c5(dev), "select_total": select_total(dev)}))
+        print(json.dumps({"hbm_kernels_at_C5_shape": hbm_kernels_c5(dev)}))
+        return
+    if a.select_only:
+        print(json.dumps({"select_total": select_total(dev)}))
         return
 
     # ---- inputs, resident in HBM ----
