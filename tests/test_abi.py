@@ -64,3 +64,30 @@ def test_product_package_does_not_touch_the_oracle():
             txt = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2510_10129_amd" not in txt and "cacheclip" not in txt.lower().replace(
                 "cacheclip hot path", ""), f
+
+
+def test_context_free_calls_reject_bad_arguments_without_a_gpu():
+    lib = cc.load_library()
+    # cc_select_noalloc checks its arguments before it touches the device
+    assert lib.cc_select_noalloc(None, None, 1, 1, 1, 0, 8, 0, 0, 0, 0, None, None) == _lib.CC_ERR_NULL
+    buf = (C.c_float * 8)()
+    out = (C.c_int32 * 8)()
+    p, o = C.cast(buf, C.c_void_p), C.cast(out, C.c_void_p)
+    for args, code in (((p, 0, 4, 4, 0, 8, 0, 0, 0, 0, o, o), _lib.CC_ERR_SHAPE),              # Q_a < 1
+                       ((p, 1, 4, 2, 0, 8, 0, 0, 0, 0, o, o), _lib.CC_ERR_SHAPE),              # ld < T
+                       ((p, 1, 131073, 131073, 0, 8, 0, 0, 0, 0, o, o), _lib.CC_ERR_WORKSPACE),  # beyond the scratch
+                       ((p, 1, 4, 4, 10001, 8, 0, 0, 0, 0, o, o), _lib.CC_ERR_SHAPE),
+                       ((p, 1, 4, 4, 100, 0, 0, 0, 0, 0, o, o), _lib.CC_ERR_SHAPE),
+                       ((p, 1, 4, 4, 100, 8, 9, 0, 0, 0, o, o), _lib.CC_ERR_SHAPE),
+                       ((p, 1, 4, 4, 100, 8, 0, 0, -1, 0, o, o), _lib.CC_ERR_SHAPE)):
+        assert lib.cc_select_noalloc(None, *args) == code, args
+        assert len(lib.cc_last_error(None)) > 0
+    assert lib.cc_debug_set_launch(None, None) == _lib.CC_ERR_NULL
+
+
+def test_launch_override_struct_matches_the_header():
+    txt = open(os.path.join(ROOT, "include", "cacheclip.h")).read()
+    body = txt[txt.index("typedef struct cc_launch_override {"):txt.index("} cc_launch_override;")]
+    fields = re.findall(r"int32_t\s+(\w+);", body)
+    assert fields == [n for n, _ in _lib.LaunchOverride._fields_]
+    assert C.sizeof(_lib.LaunchOverride) == 4 * len(fields)
