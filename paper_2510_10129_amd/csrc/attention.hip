@@ -24,11 +24,13 @@
 // SIMD belong to the same workgroup, one to group A and one to group B, and
 // the workgroup barrier separates phases: while A runs the softmax of tile t, B
 // runs P V of tile t-1 and Q K^T of tile t, and the other way round in the next
-// phase.  Group B also issues all global -> LDS loads, at the start of its
-// softmax phases (a load in the middle of an MFMA sequence stalls that wave).
+// phase.  A wave issues its global -> LDS loads at the end of its matrix phase
+// (group A the V tiles, group B the K tiles), while its SIMD partner is in the
+// vector part of its softmax: next to a partner that keeps the matrix pipe busy
+// such a load holds the issuing wave several times as long.
 //
 // K and V tiles (64 keys) go from the cache straight into LDS with 16-byte
-// global->LDS loads, row-major as they are stored, two stages each.  K
+// global->LDS loads, row-major as they are stored, three stages each.  K
 // fragments are plain 16-byte LDS reads; the V^T fragments (contraction index =
 // key) come from the row-major V tile through the transposing LDS read
 // ds_read_b64_tr_b16, so V is never transposed in registers.  Both tiles are
