@@ -84,6 +84,22 @@ def test_degenerate_cases(ctx):
     _check(ctx, big, 2000, 16)                               # T at capacity
 
 
+def test_long_inputs_with_ties_and_crowded_threshold_digit(ctx):
+    """Paths of the selection kernel that short inputs do not reach: more keys share the
+    threshold's leading digit than its LDS list holds (the remaining digits then come from further
+    passes over the scores), with and without equal scores at the threshold."""
+    rng = np.random.default_rng(6)
+    T = 100000
+    few = rng.integers(1, 5, size=(3, T)).astype(np.float32) * 0.125           # ten distinct sums: crowded, tied
+    _check(ctx, few, 2000, 16, 0, True, 7, 3)
+    _check(ctx, few, 5000, 8, 5, False, 0, 0)
+    narrow = (1.0 + rng.random((1, T)) * 0.1).astype(np.float32)                 # one binade, all distinct (mostly)
+    _check(ctx, narrow, 2000, 16, 0, True, 0, 0)
+    mixed = narrow.copy()
+    mixed[0, ::3] = np.float32(1.05)                                            # a third of the keys equal, threshold among them
+    _check(ctx, mixed, 5000, 32, 0, True, 64, 128)
+
+
 def test_strided_input_and_async_count(ctx):
     rng = np.random.default_rng(5)
     full = torch.from_numpy(rng.random((16, 1000), dtype=np.float32)).to(DEV)
