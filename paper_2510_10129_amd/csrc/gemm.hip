@@ -1059,10 +1059,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_ring16_kernel(
 
 // Tile shapes: 256x256 (8 waves of 128x64, least LDS and L2 traffic per flop, one
 // workgroup per CU), 192x256 (8 waves of 96x64, ring loop only, measured at 0.8 of the
-// large tile's rate: it pays where it saves a half-empty round; the ring loops of these two
-// use 16x16x32 MFMAs, the other shapes 32x32x16), 256x128 (8 waves of 64x64, one per CU, ring loop
-// only) and 128x128 (4 waves of 64x64, two per CU, measured at 0.55 to 0.85 of the large
-// tile's rate depending on K).  A grid runs as a whole number
+// large tile's rate: it pays where it saves a half-empty round), 256x128 (8 waves of 64x64, one
+// per CU, ring loop only) and 128x128 (4 waves of 64x64, two per CU, measured at 0.55 to 0.85 of
+// the large tile's rate depending on K).  Every shape runs the 16x16x32 ring loop when K allows
+// it, the 256x256 and 128x128 shapes the staged loop otherwise.  A grid runs as a whole number
 // of "rounds" of workgroups, so the shape is chosen per launch to minimise rounds x tile
 // cost.
 template <class BSrc, class Epi>
