@@ -353,18 +353,34 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
         constexpr int NPV = decltype(with_pv)::value ? 4 * DT : 0, NQK = 2 * KS, NALL = NPV + NQK;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         bf16x8 opnd[NALL];
+        // Order of the MFMAs when both contractions run: two of P V, two of Q K^T, and so on, so
+        // that an MFMA follows the one whose accumulator it continues four issue slots later, not
+        // two (the score tile has only two accumulation chains; back to back they wait for each
+        // other's result).
+        constexpr auto is_pv = [](int j) constexpr { return NPV != 0 && (j & 3) < 2; };
+        constexpr auto pv_of = [](int j) constexpr { return (j >> 2) * 2 + (j & 3); };
+        constexpr auto qk_of = [](int j) constexpr { return NPV != 0 ? (j >> 2) * 2 + (j & 3) - 2 : j; };
+        static_assert(NPV == 0 || NPV == NQK, "the interleaved order pairs the two contractions one to one");
+        // reads of the operands j+1 .. last (a P V operand is two reads)
+        constexpr auto reads_after = [](int j, int last) constexpr {
+            int n = 0;
+            for (int i = j + 1; i <= last; ++i) n += (NPV != 0 && (i & 3) < 2) ? 2 : 1;
+            return n;
+        };
         auto issue = [&](auto jc) __attribute__((always_inline)) {
             constexpr int j = decltype(jc)::value;
-            if constexpr (j < NPV) {
-                constexpr int ss = j / DT, dt = j % DT;
-                constexpr int at = 2 * rho(16 * ss) * D_H;
-                constexpr int at8 = 2 * rho(16 * ss + 8) * D_H;
-                const bf16x4 a0 = lds_read_tr_at<at>(vaddr[dt]);
-                const bf16x4 a1 = lds_read_tr_at<at8>(vaddr[dt]);
-                opnd[j] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-            } else if constexpr (j < NALL) {
-                constexpr int n = j - NPV, ks = n / 2, kt = n % 2;
-                opnd[j] = lds_read_b128_at<2 * kt * 8 * D_H>(kaddr[ks]);
+            if constexpr (j < NALL) {
+                if constexpr (is_pv(j)) {
+                    constexpr int p = pv_of(j), ss = p / DT, dt = p % DT;
+                    constexpr int at = 2 * rho(16 * ss) * D_H;
+                    constexpr int at8 = 2 * rho(16 * ss + 8) * D_H;
+                    const bf16x4 a0 = lds_read_tr_at<at>(vaddr[dt]);
+                    const bf16x4 a1 = lds_read_tr_at<at8>(vaddr[dt]);
+                    opnd[j] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+                } else {
+                    constexpr int n = qk_of(j), ks = n / 2, kt = n % 2;
+                    opnd[j] = lds_read_b128_at<2 * kt * 8 * D_H>(kaddr[ks]);
+                }
             }
         };
         static_for<PD>(issue);
@@ -372,14 +388,12 @@ __global__ __launch_bounds__(512, 1) void sparse_attn_kernel(
             constexpr int j = decltype(jc)::value;
             issue(std::integral_constant<int, j + PD>{});
             constexpr int last = j + PD < NALL ? j + PD : NALL - 1;
-            constexpr int npv_after = (last < NPV ? last : NPV - 1) - j > 0 ? (last < NPV ? last : NPV - 1) - j : 0;
-            constexpr int younger = (last - j) + npv_after;       // a P V operand is two reads
-            lds_wait_all_but<younger>(opnd[j]);
-            if constexpr (j < NPV) {
-                constexpr int ss = j / DT, dt = j % DT;
+            lds_wait_all_but<reads_after(j, last)>(opnd[j]);
+            if constexpr (is_pv(j)) {
+                constexpr int p = pv_of(j), ss = p / DT, dt = p % DT;
                 acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[j], pf[ss], acc_o[dt], 0, 0, 0);
             } else {
-                constexpr int n = j - NPV, ks = n / 2, kt = n % 2;
+                constexpr int n = qk_of(j), ks = n / 2, kt = n % 2;
                 s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[j], qf[ks], ks == 0 ? zero : s[kt], 0, 0, 0);
             }
         });
